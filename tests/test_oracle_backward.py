@@ -1,0 +1,99 @@
+"""Pins for the oracle's gradients (no GPU)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import flashmask_oracle as orc
+from predicates import PREDICATES
+
+KINDS = sorted(PREDICATES)
+
+
+def rand(seed, n, d):
+    rng = np.random.default_rng(seed)
+    return tuple(rng.standard_normal((n, d)) for _ in range(4))
+
+
+@pytest.mark.parametrize("kind", KINDS + ["random_intervals"])
+@pytest.mark.parametrize("n,d", [(7, 3), (16, 8)])
+def test_gradients_match_central_finite_differences(kind, n, d):
+    w = workloads.small_workload(kind, n, seed=31 + n)
+    vec = w.vectors[0]
+    q, k, v, do = rand(n, n, d)
+    scale = 0.6
+    dq, dk, dv, out, lse = orc.backward(q, k, v, do, *vec, scale)
+
+    def loss(q_, k_, v_):
+        o, _ = orc.forward(q_, k_, v_, *vec, scale)
+        return float((o * do).sum())
+
+    eps = 1e-6
+    rng = np.random.default_rng(5)
+    for arr, grad, which in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        idx = [(int(rng.integers(n)), int(rng.integers(d))) for _ in range(12)] + [(0, 0), (n - 1, d - 1)]
+        for (r, c) in idx:
+            args = [q.copy(), k.copy(), v.copy()]
+            args[which][r, c] += eps
+            up = loss(*args)
+            args[which][r, c] -= 2 * eps
+            dn = loss(*args)
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - grad[r, c]) < 1e-7 * max(1.0, abs(fd)), (kind, which, r, c, fd, grad[r, c])
+
+
+@pytest.mark.parametrize("kind", KINDS + ["random_intervals"])
+def test_gradients_match_library_autograd(kind):
+    n, d = 24, 8
+    w = workloads.small_workload(kind, n, seed=3)
+    vec = w.vectors[0]
+    q, k, v, do = rand(1, n, d)
+    scale = 1 / math.sqrt(d)
+    dq, dk, dv, out, lse = orc.backward(q, k, v, do, *vec, scale)
+    allowed = ~orc.expand_mask(*vec)
+    live = allowed.any(axis=1)
+    tq, tk, tv = (torch.from_numpy(x).clone().requires_grad_(True) for x in (q, k, v))
+    s = scale * tq @ tk.T
+    s = s.masked_fill(torch.from_numpy(~allowed), -math.inf)
+    s = torch.where(torch.from_numpy(live)[:, None], s, torch.zeros_like(s))
+    p = torch.softmax(s, dim=1) * torch.from_numpy(live)[:, None]
+    (p @ tv * torch.from_numpy(do)).sum().backward()
+    assert np.allclose(dq, tq.grad.numpy(), atol=1e-11)
+    assert np.allclose(dk, tk.grad.numpy(), atol=1e-11)
+    assert np.allclose(dv, tv.grad.numpy(), atol=1e-11)
+
+
+@pytest.mark.parametrize("kind", KINDS + ["random_intervals"])
+def test_gradient_invariants(kind):
+    n, d = 36, 8
+    w = workloads.small_workload(kind, n, seed=8)
+    vec = w.vectors[0]
+    q, k, v, do = rand(2, n, d)
+    dq, dk, dv, out, lse = orc.backward(q, k, v, do, *vec, 0.4)
+    masked = orc.expand_mask(*vec)
+    live = ~masked.all(axis=1)
+    # sum_j dV_j = sum over live rows of dO_i  (rows of P sum to one)
+    assert np.allclose(dv.sum(axis=0), do[live].sum(axis=0), atol=1e-11)
+    # a key column no row may see receives no gradient at all
+    unseen = masked.all(axis=0)
+    assert np.all(dk[unseen] == 0.0) and np.all(dv[unseen] == 0.0)
+    # a row with no visible key has zero dq
+    assert np.all(dq[~live] == 0.0)
+    # D = rowsum(dO o O) equals rowsum(P o dP)  (Algorithm 2, D pre-pass)
+    p = orc.probabilities(q, k, *vec, 0.4)
+    assert np.allclose((do * out).sum(axis=1), (p * (do @ v.T)).sum(axis=1), atol=1e-11)
+
+
+def test_partial_backward_helpers_equal_full():
+    n, d = 50, 8
+    w = workloads.small_workload("causal_document", n, seed=4)
+    vec = w.vectors[0]
+    q, k, v, do = rand(6, n, d)
+    dq, dk, dv, _, _ = orc.backward(q, k, v, do, *vec, 0.25)
+    rows = np.array([0, 49, 13, 27])
+    cols = np.array([1, 48, 20])
+    assert np.allclose(orc.backward_rows(q, k, v, do, *vec, 0.25, rows), dq[rows], atol=1e-13)
+    dk2, dv2 = orc.backward_cols(q, k, v, do, *vec, 0.25, cols)
+    assert np.allclose(dk2, dk[cols], atol=1e-13) and np.allclose(dv2, dv[cols], atol=1e-13)
