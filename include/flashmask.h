@@ -1,0 +1,154 @@
+/*
+ * flashmask.h -- C ABI of the MI355X (gfx950) FlashMask attention library.
+ *
+ * FlashMask (arXiv 2410.01359) describes an attention mask by four int32
+ * vectors over the key columns: query row i may NOT attend to key column j iff
+ *     LTS[j] <= i < LTE[j]   or   UTS[j] <= i < UTE[j]
+ * (Section 4.1; rows and columns 0-based, intervals half-open, an interval with
+ * start >= end is empty, any int32 value is accepted).  The library computes
+ * exactly the dense-mask attention of Equations 1-2 and its gradients
+ * (Algorithms 1 and 2, Section 4.4), skipping tiles that the per-block min/max
+ * tables of Section 4.2 prove fully masked.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller and must stay
+ *     valid until the stream has run past the call.  The library allocates and
+ *     frees nothing, creates no streams and never synchronises the host: work
+ *     is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns at once.
+ *   - q, k, v, out, dout, dq, dk, dv: bf16, contiguous [B, H, N, d], d innermost.
+ *   - lts, lte, uts, ute: int32, contiguous [B, N]; one mask per batch row,
+ *     shared by all heads.
+ *   - lse, and the library's own D vector: fp32 [B, H, N].
+ *   - d must be 64 or 128; N must be a positive multiple of 128; tensor
+ *     pointers must be 16-byte aligned.
+ *   - Outputs are overwritten in full.
+ *   - Return value: FM_OK (0) or a negative FM_ERR_* code.  Only conditions the
+ *     host can see are checked; bound VALUES live on the device and are not
+ *     validated (the comparison above is defined for every int32).
+ *   - Calls on different streams need different workspaces.
+ */
+#ifndef FLASHMASK_H
+#define FLASHMASK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  FM_OK = 0,
+  FM_ERR_NULL = -1,      /* a required pointer is NULL */
+  FM_ERR_SHAPE = -2,     /* B, H, N <= 0, d not in {64,128}, N not a multiple of 128, bad block size */
+  FM_ERR_ALIGN = -3,     /* a tensor pointer is not 16-byte aligned */
+  FM_ERR_WORKSPACE = -4, /* workspace is NULL or smaller than flashmask_workspace_bytes() */
+  FM_ERR_HIP = -5,       /* a kernel launch failed; see flashmask_last_hip_error() */
+  FM_ERR_ARG = -6        /* unknown pass id or other bad scalar argument */
+};
+
+/* Pass ids for flashmask_workspace_bytes / flashmask_tile_shape. */
+enum {
+  FM_PASS_FWD = 0,      /* forward tile loop (Algorithm 1) */
+  FM_PASS_BWD_DKDV = 1, /* backward, column-parallel dK/dV loop (Algorithm 2) */
+  FM_PASS_BWD_DQ = 2,   /* backward, row-parallel dQ loop (Algorithm 2's dQ update, run per query block) */
+  FM_PASS_BWD = 3       /* whole backward call (workspace query only) */
+};
+
+/* Tile-class byte written by flashmask_classify (Equation 4).
+ * Low two bits: kind.  Bits 4 / 5: a partially masked tile needs the element
+ * mask of the lower-triangle pair / of the upper-triangle pair. */
+enum {
+  FM_TILE_UNMASKED = 0,
+  FM_TILE_PARTIAL = 1,
+  FM_TILE_FULLY = 2,
+  FM_TILE_NEED_LT = 1 << 4,
+  FM_TILE_NEED_UT = 1 << 5
+};
+
+/*
+ * Forward pass: Algorithm 1 (its outputs O and L), i.e. Equations 1-2 with
+ * S = scale * Q K^T, masked scores = -inf, out = softmax(S) V and
+ * lse_i = log sum_j exp(S_ij) (natural log, of the scaled scores).
+ * A query row whose keys are all masked gets out = 0 and lse = -inf.
+ *
+ *   q, k, v        in   bf16 [B,H,N,d]
+ *   lts..ute       in   int32 [B,N]
+ *   scale          in   multiplies Q K^T (1/sqrt(d) in the paper's Equation 1)
+ *   out            out  bf16 [B,H,N,d]
+ *   lse            out  fp32 [B,H,N]
+ *   workspace      scratch of at least flashmask_workspace_bytes(FM_PASS_FWD, ...)
+ *                  bytes, 256-byte aligned; contents undefined afterwards.
+ */
+int flashmask_fwd(const void* q, const void* k, const void* v,
+                  const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                  float scale, void* out, float* lse,
+                  int B, int H, int N, int d,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward pass: Algorithm 2.  Given the forward's out and lse and the upstream
+ * gradient dout, writes dq, dk, dv (bf16 [B,H,N,d]):
+ *   P = exp(S - lse), dV = P^T dO, dP = dO V^T, D_i = sum_c dO_ic O_ic,
+ *   dS = P o (dP - D), dQ = scale dS K, dK = scale dS^T Q.
+ * Rows with lse = -inf contribute nothing and get dq = 0.
+ * The dQ accumulation runs per query block in a fixed order, so results are
+ * bit-reproducible run to run (the paper's kernel needs a switch for that,
+ * Section 5.2).
+ *   workspace: at least flashmask_workspace_bytes(FM_PASS_BWD, ...) bytes.
+ */
+int flashmask_bwd(const void* q, const void* k, const void* v,
+                  const void* out, const float* lse, const void* dout,
+                  const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                  float scale, void* dq, void* dk, void* dv,
+                  int B, int H, int N, int d,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of scratch a call of the given pass needs (FM_PASS_FWD or FM_PASS_BWD).
+ * Returns 0 for an invalid shape or pass.  Host-only, no device work. */
+size_t flashmask_workspace_bytes(int pass, int B, int H, int N, int d);
+
+/*
+ * Preprocessing step of Section 4.2 (Algorithm 1 "precompute the min and max
+ * row index"): for every block of block_c key columns, the max and min of each
+ * bound vector.
+ *   minmax  out  int32 [B, 8, T_c], T_c = ceil(N / block_c), rows in the order
+ *                LTStart^max, LTStart^min, LTEnd^max, LTEnd^min,
+ *                UTStart^max, UTStart^min, UTEnd^max, UTEnd^min.
+ * block_c must be a positive multiple of 32; any N > 0 is accepted here (a
+ * ragged last block covers the columns that exist).
+ */
+int flashmask_preprocess(const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                         int B, int N, int block_c, int32_t* minmax, void* hip_stream);
+
+/*
+ * Tile classification of Equation 4, as the skip tests and element-mask tests
+ * of Algorithm 1 apply it, for every tile of block_r rows x block_c columns:
+ * with r0 = i*block_r, r1 = min(r0 + block_r, N),
+ *   fully(X)   = r0 >= XStart^max_j and r1 <= XEnd^min_j
+ *   partial(X) = r1 >  XStart^min_j and r0 <  XEnd^max_j      X in {LT, UT}
+ *   class = FULLY if fully(LT) or fully(UT); else PARTIAL | NEED_X bits if any
+ *   partial(X); else UNMASKED.
+ *   minmax  in   int32 [B, 8, T_c] as written by flashmask_preprocess
+ *   cls     out  uint8 [B, T_r, T_c]
+ * The attention kernels evaluate the same predicate on the fly; this entry
+ * point exists so the tables can be checked bit for bit.
+ */
+int flashmask_classify(const int32_t* minmax, int B, int N, int block_r, int block_c,
+                       uint8_t* cls, void* hip_stream);
+
+/* Tile shape (rows x key columns) at which the given pass classifies and skips
+ * tiles.  Host-only. */
+int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c);
+
+/* Static, human-readable text for an FM_* code. */
+const char* flashmask_strerror(int code);
+
+/* Text of the last HIP error behind an FM_ERR_HIP on this thread ("" if none). */
+const char* flashmask_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHMASK_H */

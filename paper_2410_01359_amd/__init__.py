@@ -1,0 +1,9 @@
+"""MI355X-native FlashMask attention (arXiv 2410.01359): thin Python binding
+over the C-ABI HIP library.  Every step of the path runs in the HIP kernels;
+this package only marshals arguments and owns device memory through torch."""
+from .binding import (  # noqa: F401
+    FM_PASS_BWD, FM_PASS_BWD_DKDV, FM_PASS_BWD_DQ, FM_PASS_FWD,
+    FlashMaskError, flashmask_bwd, flashmask_classify, flashmask_fwd,
+    flashmask_preprocess, flashmask_tile_shape, flashmask_workspace_bytes,
+    library_path, load_library,
+)

@@ -1,0 +1,177 @@
+// C ABI of the library: argument validation, workspace carving, launches.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/flashmask.h"
+#include "fm_kernels.h"
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e) {
+  snprintf(g_hip_error, sizeof(g_hip_error), "%s", hipGetErrorString(e));
+  return FM_ERR_HIP;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_shape(int B, int H, int N, int d) {
+  if (B <= 0 || H <= 0 || N <= 0) return FM_ERR_SHAPE;
+  if (d != 64 && d != 128) return FM_ERR_SHAPE;
+  if (N % 128 != 0) return FM_ERR_SHAPE;
+  if ((long long)B * H * (N / 64) >= (1ll << 31) / 8) return FM_ERR_SHAPE;
+  return FM_OK;
+}
+
+// Workspace layout of a pass: tables, work counts and launch order.
+struct PassSpace {
+  size_t minmax, work, order, total;
+};
+PassSpace pass_space(int B, int H, int N, int block_r, int block_c, bool row_units, size_t start) {
+  PassSpace s;
+  const size_t t_c = (N + block_c - 1) / block_c, t_r = (N + block_r - 1) / block_r;
+  const size_t per = row_units ? t_r : t_c;
+  s.minmax = start;
+  s.work = align_up(s.minmax + (size_t)B * 8 * t_c * 4, 256);
+  s.order = align_up(s.work + (size_t)B * per * 4, 256);
+  s.total = align_up(s.order + (size_t)fm_order_slots((int)((size_t)B * H * per)) * 4, 256);
+  return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* flashmask_strerror(int code) {
+  switch (code) {
+    case FM_OK: return "ok";
+    case FM_ERR_NULL: return "a required pointer is NULL";
+    case FM_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, d in {64,128}, N a multiple of 128)";
+    case FM_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+    case FM_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
+    case FM_ERR_HIP: return "HIP launch failed (see flashmask_last_hip_error)";
+    case FM_ERR_ARG: return "bad scalar argument";
+    default: return "unknown flashmask error code";
+  }
+}
+
+const char* flashmask_last_hip_error(void) { return g_hip_error; }
+
+int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c) {
+  if (!block_r || !block_c) return FM_ERR_NULL;
+  if (d != 64 && d != 128) return FM_ERR_SHAPE;
+  switch (pass) {
+    case FM_PASS_FWD: *block_r = FM_FWD_BR; *block_c = FM_FWD_BC; return FM_OK;
+    case FM_PASS_BWD_DKDV: *block_r = FM_DKDV_BR; *block_c = FM_DKDV_BC; return FM_OK;
+    case FM_PASS_BWD_DQ: *block_r = FM_DQ_BR; *block_c = FM_DQ_BC; return FM_OK;
+    default: return FM_ERR_ARG;
+  }
+}
+
+size_t flashmask_workspace_bytes(int pass, int B, int H, int N, int d) {
+  if (check_shape(B, H, N, d) != FM_OK) return 0;
+  if (pass == FM_PASS_FWD) return pass_space(B, H, N, FM_FWD_BR, FM_FWD_BC, true, 0).total;
+  if (pass == FM_PASS_BWD) {
+    const PassSpace dq = pass_space(B, H, N, FM_DQ_BR, FM_DQ_BC, true, 0);
+    const PassSpace kv = pass_space(B, H, N, FM_DKDV_BR, FM_DKDV_BC, false, dq.total);
+    return kv.total + align_up((size_t)B * H * N * 4, 256);  // + D vector
+  }
+  return 0;
+}
+
+int flashmask_preprocess(const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute, int B, int N,
+                         int block_c, int32_t* minmax, void* hip_stream) {
+  if (!lts || !lte || !uts || !ute || !minmax) return FM_ERR_NULL;
+  if (B <= 0 || N <= 0 || block_c <= 0 || block_c % 32 != 0) return FM_ERR_SHAPE;
+  hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, block_c, minmax, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FM_OK : hip_fail(e);
+}
+
+int flashmask_classify(const int32_t* minmax, int B, int N, int block_r, int block_c, uint8_t* cls, void* hip_stream) {
+  if (!minmax || !cls) return FM_ERR_NULL;
+  if (B <= 0 || N <= 0 || block_c <= 0 || block_r <= 0) return FM_ERR_SHAPE;
+  const long long t_r = (N + block_r - 1) / block_r;
+  if (t_r > 65535 || B > 65535) return FM_ERR_SHAPE;
+  hipError_t e = fm_launch_classify(minmax, B, N, block_r, block_c, cls, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FM_OK : hip_fail(e);
+}
+
+int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
+                  const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H, int N,
+                  int d, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!q || !k || !v || !lts || !lte || !uts || !ute || !out || !lse) return FM_ERR_NULL;
+  if (int rc = check_shape(B, H, N, d)) return rc;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lts) || misaligned(lte) ||
+      misaligned(uts) || misaligned(ute) || misaligned(lse))
+    return FM_ERR_ALIGN;
+  const size_t need = flashmask_workspace_bytes(FM_PASS_FWD, B, H, N, d);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FM_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const PassSpace sp = pass_space(B, H, N, FM_FWD_BR, FM_FWD_BC, true, 0);
+  int* minmax = (int*)(ws + sp.minmax);
+  int* work = (int*)(ws + sp.work);
+  int* order = (int*)(ws + sp.order);
+  hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_FWD_BC, minmax, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_row_order(minmax, B, H, N, FM_FWD_BR, FM_FWD_BC, work, order, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  FmFwdArgs a;
+  a.q = q; a.k = k; a.v = v;
+  a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
+  a.minmax = minmax; a.order = order;
+  a.out = out; a.lse = lse; a.scale = scale;
+  a.B = B; a.H = H; a.N = N; a.d = d;
+  a.slots = fm_order_slots(B * H * (N / FM_FWD_BR));
+  e = fm_launch_fwd(a, stream);
+  return e == hipSuccess ? FM_OK : hip_fail(e);
+}
+
+int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse, const void* dout,
+                  const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute, float scale,
+                  void* dq, void* dk, void* dv, int B, int H, int N, int d, void* workspace, size_t workspace_bytes,
+                  void* hip_stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !lts || !lte || !uts || !ute || !dq || !dk || !dv) return FM_ERR_NULL;
+  if (int rc = check_shape(B, H, N, d)) return rc;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dout) || misaligned(dq) ||
+      misaligned(dk) || misaligned(dv) || misaligned(lts) || misaligned(lte) || misaligned(uts) || misaligned(ute) ||
+      misaligned(lse))
+    return FM_ERR_ALIGN;
+  const size_t need = flashmask_workspace_bytes(FM_PASS_BWD, B, H, N, d);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FM_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const PassSpace sq = pass_space(B, H, N, FM_DQ_BR, FM_DQ_BC, true, 0);
+  const PassSpace skv = pass_space(B, H, N, FM_DKDV_BR, FM_DKDV_BC, false, sq.total);
+  FmBwdArgs a;
+  a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
+  a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
+  a.minmax_dq = (int*)(ws + sq.minmax); a.order_dq = (int*)(ws + sq.order);
+  a.minmax_dkdv = (int*)(ws + skv.minmax); a.order_dkdv = (int*)(ws + skv.order);
+  a.dvec = (float*)(ws + skv.total);
+  a.dq = dq; a.dk = dk; a.dv = dv; a.scale = scale;
+  a.B = B; a.H = H; a.N = N; a.d = d;
+  a.slots_dq = fm_order_slots(B * H * (N / FM_DQ_BR));
+  a.slots_dkdv = fm_order_slots(B * H * (N / FM_DKDV_BC));
+  hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_row_order(a.minmax_dq, B, H, N, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.order), stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DKDV_BC, (int*)(ws + skv.minmax), stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_col_order(a.minmax_dkdv, B, H, N, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
+                          (int*)(ws + skv.order), stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_dvec(a, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_bwd_dkdv(a, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = fm_launch_bwd_dq(a, stream);
+  return e == hipSuccess ? FM_OK : hip_fail(e);
+}
+
+}  // extern "C"

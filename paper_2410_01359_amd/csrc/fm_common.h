@@ -1,0 +1,83 @@
+// Shared device-side definitions for the gfx950 FlashMask kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fm {
+
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define FM_LDS __attribute__((address_space(3)))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Rows of the preprocessing table (Section 4.2), per batch row: [8][T_c].
+enum { LTS_MAX = 0, LTS_MIN, LTE_MAX, LTE_MIN, UTS_MAX, UTS_MIN, UTE_MAX, UTE_MIN };
+
+// Tile classes (Equation 4); same encoding as FM_TILE_* in flashmask.h.
+enum { T_UNMASKED = 0, T_PARTIAL = 1, T_FULLY = 2, T_NEED_LT = 16, T_NEED_UT = 32 };
+
+struct MinMax8 {
+  int v[8];
+};
+
+// Equation 4 for the row range [r0, r1) against one key block's min/max values.
+__device__ __forceinline__ int classify_tile(int r0, int r1, const MinMax8& t) {
+  const bool full_lt = (r0 >= t.v[LTS_MAX]) && (r1 <= t.v[LTE_MIN]);
+  const bool full_ut = (r0 >= t.v[UTS_MAX]) && (r1 <= t.v[UTE_MIN]);
+  if (full_lt || full_ut) return T_FULLY;
+  const bool part_lt = (r1 > t.v[LTS_MIN]) && (r0 < t.v[LTE_MAX]);
+  const bool part_ut = (r1 > t.v[UTS_MIN]) && (r0 < t.v[UTE_MAX]);
+  if (part_lt || part_ut) return T_PARTIAL | (part_lt ? T_NEED_LT : 0) | (part_ut ? T_NEED_UT : 0);
+  return T_UNMASKED;
+}
+
+__device__ __forceinline__ MinMax8 load_minmax(const int* __restrict__ table, int t_c, int j) {
+  MinMax8 t;
+#pragma unroll
+  for (int a = 0; a < 8; ++a) t.v[a] = table[a * t_c + j];
+  return t;
+}
+
+// D(32x32) += A(32x16) * B(16x32), bf16 inputs, fp32 accumulate.
+// Lane l holds A[m = l%32][k = 8*(l/32) + t], B[k = 8*(l/32) + t][n = l%32], t = 0..7,
+// and D[m = 8*(r/4) + 4*(l/32) + r%4][n = l%32] in register r = 0..15.
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// LDS transpose read: within each block of 16 lanes, lane i addresses 4
+// consecutive 16-bit elements of row (i/4), columns 4*(i%4)..+3 of a 4 x 16
+// matrix; it receives column i of that matrix (4 values, one per row).
+__device__ __forceinline__ bf16x4 lds_read_tr16(const char* lds_generic) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FM_LDS bf16x4*)lds_generic);
+}
+
+__device__ __forceinline__ bf16x8 cat4(bf16x4 lo, bf16x4 hi) {
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Exchange with the lane 32 away: returns the partner's value.
+__device__ __forceinline__ float partner32(float x) {
+  int xi = __builtin_bit_cast(int, x);
+  // permlane32_swap(a, b): r[0] = {a.lo, b.lo}, r[1] = {a.hi, b.hi} (lo/hi = lanes 0-31 / 32-63)
+  auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  // lanes 0-31: r[1] holds x of lanes 32-63; lanes 32-63: r[0] holds x of lanes 0-31
+  int other = (threadIdx.x & 32) ? r[0] : r[1];
+  return __builtin_bit_cast(float, other);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ u32x4 ldg16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+}  // namespace fm

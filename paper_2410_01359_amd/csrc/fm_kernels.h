@@ -1,0 +1,57 @@
+// Host-side launchers of the gfx950 FlashMask kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// Number of launch slots for `units` work units: 8 interleaved groups.
+inline int fm_order_slots(int units) { return ((units + 7) / 8) * 8; }
+
+struct FmShape {
+  int B, H, N, d;
+};
+
+// Tile shapes (rows x key columns) each pass classifies at.
+constexpr int FM_FWD_BR = 128, FM_FWD_BC = 64;
+constexpr int FM_DQ_BR = 128, FM_DQ_BC = 64;
+constexpr int FM_DKDV_BR = 64, FM_DKDV_BC = 128;
+
+hipError_t fm_launch_preprocess(const int* lts, const int* lte, const int* uts, const int* ute, int B, int N,
+                                int block_c, int* minmax, hipStream_t stream);
+hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int block_c, uint8_t* cls,
+                              hipStream_t stream);
+// work: int[B * T_r] (resp. B * T_c); order: int[fm_order_slots(B*H*T)].
+hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
+                               int* order, hipStream_t stream);
+hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
+                               int* order, hipStream_t stream);
+
+struct FmFwdArgs {
+  const void *q, *k, *v;
+  const int *lts, *lte, *uts, *ute;
+  const int* minmax;  // [B][8][T_c] at FM_FWD_BC
+  const int* order;   // launch slots -> unit (b*H + h)*T_r + i, or -1
+  void* out;
+  float* lse;
+  float scale;
+  int B, H, N, d;
+  int slots;
+};
+hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream);
+
+struct FmBwdArgs {
+  const void *q, *k, *v, *out, *dout;
+  const float* lse;
+  const int *lts, *lte, *uts, *ute;
+  const int* minmax_dq;    // [B][8][T_c] at FM_DQ_BC
+  const int* order_dq;
+  const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
+  const int* order_dkdv;
+  float* dvec;             // D = rowsum(dO o O), [B,H,N]
+  void *dq, *dk, *dv;
+  float scale;
+  int B, H, N, d;
+  int slots_dq, slots_dkdv;
+};
+hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream);
+hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream);
+hipError_t fm_launch_bwd_dkdv(const FmBwdArgs& a, hipStream_t stream);

@@ -1,0 +1,212 @@
+// Preprocessing (Section 4.2): per key-block min/max of the four bound vectors,
+// the exported tile-class dump (Equation 4), and the per-unit work counts the
+// launch order is built from.
+#include "fm_common.h"
+#include "fm_kernels.h"
+
+namespace fm {
+
+// One wave per (batch row, key block).  Lanes stride over the block's columns,
+// then a butterfly over the 64 lanes leaves the 8 results in every lane.
+__global__ __launch_bounds__(256) void preprocess_kernel(const int* __restrict__ lts, const int* __restrict__ lte,
+                                                         const int* __restrict__ uts, const int* __restrict__ ute,
+                                                         int n, int block_c, int t_c, int total_blocks,
+                                                         int* __restrict__ minmax) {
+  const int lane = threadIdx.x & 63;
+  const int blk = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blk >= total_blocks) return;
+  const int b = blk / t_c, j = blk - b * t_c;
+  const int c0 = j * block_c;
+  const int c1 = min(c0 + block_c, n);
+  const int* vec[4] = {lts + (size_t)b * n, lte + (size_t)b * n, uts + (size_t)b * n, ute + (size_t)b * n};
+  int mx[4], mn[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    mx[a] = INT32_MIN;
+    mn[a] = INT32_MAX;
+  }
+  for (int c = c0 + lane; c < c1; c += 64) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int x = vec[a][c];
+      mx[a] = max(mx[a], x);
+      mn[a] = min(mn[a], x);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      mx[a] = max(mx[a], __shfl_xor(mx[a], off, 64));
+      mn[a] = min(mn[a], __shfl_xor(mn[a], off, 64));
+    }
+  }
+  if (lane == 0) {
+    int* out = minmax + (size_t)b * 8 * t_c;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      out[(2 * a) * t_c + j] = mx[a];
+      out[(2 * a + 1) * t_c + j] = mn[a];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void classify_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
+                                                       int t_c, uint8_t* __restrict__ cls) {
+  const int b = blockIdx.z, i = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= t_c) return;
+  const MinMax8 t = load_minmax(minmax + (size_t)b * 8 * t_c, t_c, j);
+  const int r0 = i * block_r;
+  const int r1 = min(r0 + block_r, n);
+  cls[((size_t)b * t_r + i) * t_c + j] = (uint8_t)classify_tile(r0, r1, t);
+}
+
+// Work of one row block = number of key blocks that are not fully masked.
+// One wave per (batch row, row block); lanes stride over the key blocks.
+__global__ __launch_bounds__(256) void row_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
+                                                       int t_c, int total_units, int* __restrict__ work) {
+  const int lane = threadIdx.x & 63;
+  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (u >= total_units) return;
+  const int b = u / t_r, i = u - b * t_r;
+  const int r0 = i * block_r, r1 = min(r0 + block_r, n);
+  const int* table = minmax + (size_t)b * 8 * t_c;
+  int cnt = 0;
+  for (int j = lane; j < t_c; j += 64) cnt += (classify_tile(r0, r1, load_minmax(table, t_c, j)) != T_FULLY);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+  if (lane == 0) work[u] = cnt;
+}
+
+// Work of one key block = number of row blocks that are not fully masked.
+__global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
+                                                       int t_c, int total_units, int* __restrict__ work) {
+  const int lane = threadIdx.x & 63;
+  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (u >= total_units) return;
+  const int b = u / t_c, j = u - b * t_c;
+  const MinMax8 t = load_minmax(minmax + (size_t)b * 8 * t_c, t_c, j);
+  int cnt = 0;
+  for (int i = lane; i < t_r; i += 64) {
+    const int r0 = i * block_r, r1 = min(r0 + block_r, n);
+    cnt += (classify_tile(r0, r1, t) != T_FULLY);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+  if (lane == 0) work[u] = cnt;
+}
+
+// Launch order (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8
+// and workgroups start in index order as slots free up.  Units are therefore
+// dealt into 8 groups (one per XCD: by head when the head count is a multiple
+// of 8, so that the units sharing one head's K/V also share one L2), each
+// group is sorted heaviest first (work quantised to 512 levels), and the
+// groups are interleaved: order[8*s + g] = s-th heaviest unit of group g.
+// In-order dispatch of that list is longest-job-first list scheduling per XCD.
+// Slots with no unit hold -1.  Single workgroup of 1024 threads.
+constexpr int kLevels = 512;
+constexpr int kGroups = 8;
+
+// work is indexed [batch row][block]; a unit is (batch row, head, block).
+__global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ work, int batch, int heads,
+                                                     int units_per_bh, int max_work, int slots,
+                                                     int* __restrict__ order) {
+  __shared__ int hist[kGroups * kLevels];
+  __shared__ int wave_sum[16];
+  const int tid = threadIdx.x;
+  const int total_units = batch * heads * units_per_bh;
+  const bool by_head = ((batch * heads) % kGroups) == 0;
+  for (int w = tid; w < kGroups * kLevels; w += 1024) hist[w] = 0;
+  for (int s = tid; s < slots; s += 1024) order[s] = -1;
+  __syncthreads();
+  auto key_of = [&](int u) {
+    const int g = by_head ? (u / units_per_bh) % kGroups : u % kGroups;
+    const int w_u = work[(u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh];
+    const int lvl = (int)(((long long)w_u * (kLevels - 1)) / (max_work > 0 ? max_work : 1));
+    return g * kLevels + (kLevels - 1 - min(max(lvl, 0), kLevels - 1));
+  };
+  for (int u = tid; u < total_units; u += 1024) atomicAdd(&hist[key_of(u)], 1);
+  __syncthreads();
+  // exclusive scan of hist (4096 entries, 4 per thread)
+  int v[4], sum = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    v[e] = hist[tid * 4 + e];
+    sum += v[e];
+  }
+  int incl = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(incl, off, 64);
+    if ((tid & 63) >= off) incl += y;
+  }
+  if ((tid & 63) == 63) wave_sum[tid >> 6] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < (tid >> 6); ++w) base += wave_sum[w];
+  int run = base + incl - sum;
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    hist[tid * 4 + e] = run;  // start offset of this key in the concatenated sorted lists
+    run += v[e];
+  }
+  __syncthreads();
+  __shared__ int group_start[kGroups];
+  if (tid < kGroups) group_start[tid] = hist[tid * kLevels];
+  __syncthreads();
+  for (int u = tid; u < total_units; u += 1024) {
+    const int key = key_of(u);
+    const int g = key / kLevels;
+    const int pos = atomicAdd(&hist[key], 1) - group_start[g];
+    const int slot = pos * kGroups + g;
+    if (slot < slots) order[slot] = u;
+  }
+}
+
+}  // namespace fm
+
+using namespace fm;
+
+hipError_t fm_launch_preprocess(const int* lts, const int* lte, const int* uts, const int* ute, int B, int N,
+                                int block_c, int* minmax, hipStream_t stream) {
+  const int t_c = (N + block_c - 1) / block_c;
+  const int total = B * t_c;
+  hipLaunchKernelGGL(preprocess_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, lts, lte, uts, ute, N, block_c,
+                     t_c, total, minmax);
+  return hipGetLastError();
+}
+
+hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int block_c, uint8_t* cls,
+                              hipStream_t stream) {
+  const int t_c = (N + block_c - 1) / block_c;
+  const int t_r = (N + block_r - 1) / block_r;
+  hipLaunchKernelGGL(classify_kernel, dim3((t_c + 255) / 256, t_r, B), dim3(256), 0, stream, minmax, N, block_r, t_r,
+                     t_c, cls);
+  return hipGetLastError();
+}
+
+hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
+                               int* order, hipStream_t stream) {
+  const int t_c = (N + block_c - 1) / block_c;
+  const int t_r = (N + block_r - 1) / block_r;
+  const int total = B * t_r;
+  hipLaunchKernelGGL(row_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
+                     work);
+  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, B, H, t_r, t_c,
+                     fm_order_slots(B * H * t_r), order);
+  return hipGetLastError();
+}
+
+hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
+                               int* order, hipStream_t stream) {
+  const int t_c = (N + block_c - 1) / block_c;
+  const int t_r = (N + block_r - 1) / block_r;
+  const int total = B * t_c;
+  hipLaunchKernelGGL(col_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
+                     work);
+  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, B, H, t_c, t_r,
+                     fm_order_slots(B * H * t_c), order);
+  return hipGetLastError();
+}
