@@ -80,4 +80,55 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 
 __device__ __forceinline__ u32x4 ldg16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 
+// Ordered compaction shared by the tile loops: every thread of a 256-thread
+// workgroup offers one candidate per pass (live or not, with its list entry);
+// live entries are appended to list[] in candidate order.  `running` carries
+// the count across passes.  Contains two barriers.
+__device__ __forceinline__ void append_live(bool live, int entry, int* list, int* wave_cnt, int& running) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned long long ballot = __ballot(live);
+  const int prefix = __popcll(ballot & ((1ull << lane) - 1ull));
+  if (lane == 0) wave_cnt[wave] = __popcll(ballot);
+  __syncthreads();
+  int off = running, tot = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int cw = wave_cnt[w];
+    if (w < wave) off += cw;
+    tot += cw;
+  }
+  if (live) list[off + prefix] = entry;
+  running += tot;
+  __syncthreads();
+}
+
+// Row-parallel loops: classify key blocks [j_begin, j_end) against rows [r0, r1)
+// (Equation 4) and list the ones that are not fully masked, in order, as
+// j | class << 24.  Returns the count (uniform over the workgroup).
+__device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ table, int t_c, int j_begin, int j_end,
+                                                     int r0, int r1, int* list, int* wave_cnt) {
+  int running = 0;
+  for (int base = j_begin; base < j_end; base += 256) {
+    const int j = base + threadIdx.x;
+    int cls = T_FULLY;
+    if (j < j_end) cls = classify_tile(r0, r1, load_minmax(table, t_c, j));
+    append_live(cls != T_FULLY, j | (cls << 24), list, wave_cnt, running);
+  }
+  return running;
+}
+
+// Column-parallel loop: classify row blocks [i_begin, i_end) of block_r rows
+// against one key block's min/max values; entries are i | class << 24.
+__device__ __forceinline__ int build_live_row_blocks(const MinMax8& t, int n, int block_r, int i_begin, int i_end,
+                                                     int* list, int* wave_cnt) {
+  int running = 0;
+  for (int base = i_begin; base < i_end; base += 256) {
+    const int i = base + threadIdx.x;
+    int cls = T_FULLY;
+    if (i < i_end) cls = classify_tile(i * block_r, min((i + 1) * block_r, n), t);
+    append_live(cls != T_FULLY, i | (cls << 24), list, wave_cnt, running);
+  }
+  return running;
+}
+
 }  // namespace fm

@@ -32,35 +32,6 @@ struct FwdCfg {
   static constexpr int NCH = KT * D / 8 / 256;  // 16-byte chunks per thread per matrix
 };
 
-// Classify key blocks [j_begin, j_end) for rows [r0, r1) and write the live ones,
-// in order, to list[] as j | class << 24.  Returns the count (uniform).
-__device__ __forceinline__ int build_live_list(const int* __restrict__ table, int t_c, int j_begin, int j_end, int r0,
-                                               int r1, int* list, int* wave_cnt) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int running = 0;
-  for (int base = j_begin; base < j_end; base += 256) {
-    const int j = base + tid;
-    int cls = T_FULLY;
-    if (j < j_end) cls = classify_tile(r0, r1, load_minmax(table, t_c, j));
-    const bool live = cls != T_FULLY;
-    const unsigned long long ballot = __ballot(live);
-    const int prefix = __popcll(ballot & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_cnt[wave] = __popcll(ballot);
-    __syncthreads();
-    int off = running, tot = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int cw = wave_cnt[w];
-      if (w < wave) off += cw;
-      tot += cw;
-    }
-    if (live) list[off + prefix] = j | (cls << 24);
-    running += tot;
-    __syncthreads();
-  }
-  return running;
-}
-
 template <int D, int QB>
 __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) {
   using C = FwdCfg<D, QB>;
@@ -145,8 +116,8 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
   }
 
   for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
-    const int n_live = build_live_list(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N), list,
-                                       wave_cnt);
+    const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N),
+                                             list, wave_cnt);
     if (n_live == 0) continue;
     const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
     FM_ISSUE_LOADS(first_entry);
