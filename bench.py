@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlashMask hot path on one MI355X.
+
+One "step" = one forward + one backward pass of the whole C-ABI path
+(preprocessing, launch order, tile loops, D pre-pass) over one batch of
+synthetic bf16 input already resident in HBM.  Throughput counts only unmasked
+FLOPs: 4*d per unmasked score element forward, 2.5x that backward.
+
+Prints ONE JSON line ("Measurement").
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+DEFAULT_WORKLOAD = "5"
+
+
+def hip_runtime():
+    lib = ctypes.CDLL("libamdhip64.so")
+    lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    lib.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    return lib
+
+
+def make_events(hip, n):
+    arr = (ctypes.c_void_p * n)()
+    for i in range(n):
+        ev = ctypes.c_void_p()
+        rc = hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        arr[i] = ev
+    return arr
+
+
+def elapsed(hip, a, b):
+    ms = ctypes.c_float()
+    rc = hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+    if rc != 0:
+        raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+    return float(ms.value)
+
+
+def device_inputs(w, torch):
+    """bf16 ~N(0,1) tensors drawn on the device from a seeded generator (same
+    distribution as the parity inputs; the bench needs no host copy)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed)
+    shape = (w.B, w.H, w.N, w.d)
+    t = {n: torch.randn(shape, device="cuda", dtype=torch.float32, generator=g).bfloat16() for n in ("q", "k", "v", "dout")}
+    vecs = tuple(torch.from_numpy(x).cuda() for x in w.stacked_vectors())
+    return t, vecs
+
+
+def run_workload(name, steps, warmup, torch, fm, orc, workloads, hip, with_events):
+    w = workloads.config(name)
+    t, vecs = device_inputs(w, torch)
+    ws = torch.empty(max(fm.flashmask_workspace_bytes(fm.FM_PASS_BWD, w.B, w.H, w.N, w.d),
+                         fm.flashmask_workspace_bytes(fm.FM_PASS_FWD, w.B, w.H, w.N, w.d)),
+                     dtype=torch.uint8, device="cuda")
+    n_unmasked = sum(orc.count_unmasked_elements(*v) for v in w.vectors) * w.H
+    f_fwd = 4.0 * w.d * n_unmasked
+    f_total = 3.5 * f_fwd
+    cls128 = [orc.classify_tiles_fast(orc.minmax_tables(*v, 128), w.N, 128, 128) for v in w.vectors]
+    rho = float(np.mean([orc.block_sparsity(c) for c in cls128]))
+    f_tile = 3.5 * sum(orc.flops_tile(c, w.H, w.d)[0] for c in cls128)
+
+    lib = fm.load_library()
+
+    def step(ev_f=None, ev_b=None):
+        if ev_f is not None:
+            lib.flashmask_profile_events(ev_f, 3)
+        out, lse = fm.flashmask_fwd(t["q"], t["k"], t["v"], *vecs, w.scale, workspace=ws)
+        if ev_b is not None:
+            lib.flashmask_profile_events(ev_b, 5)
+        fm.flashmask_bwd(t["q"], t["k"], t["v"], out, lse, t["dout"], *vecs, w.scale, workspace=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(make_events(hip, 3), make_events(hip, 5)) for _ in range(steps)] if with_events else [(None, None)] * steps
+    t0 = time.perf_counter()
+    for ev_f, ev_b in evs:
+        step(ev_f, ev_b)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    lib.flashmask_profile_events(None, 0)
+
+    res = {"workload": name, "ms_per_step": wall_ms, "tflops": f_total / wall_ms / 1e9, "block_sparsity": rho,
+           "unmasked_tflop": f_total / 1e12, "tile_tflop": f_tile / 1e12, "workload_obj": w}
+    if with_events:
+        stage = {"fwd_setup": [], "fwd_tiles": [], "bwd_setup": [], "bwd_dvec": [], "bwd_dkdv": [], "bwd_dq": []}
+        fwd_ms, bwd_ms = [], []
+        for ev_f, ev_b in evs:
+            stage["fwd_setup"].append(elapsed(hip, ev_f[0], ev_f[1]))
+            stage["fwd_tiles"].append(elapsed(hip, ev_f[1], ev_f[2]))
+            stage["bwd_setup"].append(elapsed(hip, ev_b[0], ev_b[1]))
+            stage["bwd_dvec"].append(elapsed(hip, ev_b[1], ev_b[2]))
+            stage["bwd_dkdv"].append(elapsed(hip, ev_b[2], ev_b[3]))
+            stage["bwd_dq"].append(elapsed(hip, ev_b[3], ev_b[4]))
+            fwd_ms.append(elapsed(hip, ev_f[0], ev_f[2]))
+            bwd_ms.append(elapsed(hip, ev_b[0], ev_b[4]))
+        res["stage_ms"] = {k: float(np.mean(v)) for k, v in stage.items()}
+        res["fwd_ms"], res["bwd_ms"] = float(np.mean(fwd_ms)), float(np.mean(bwd_ms))
+        # algorithmic FLOPs of each tile loop per launch: matrix products per tile x 2*d per unmasked element
+        res["kernel_flop"] = {"fwd_tiles": 4.0 * w.d * n_unmasked, "bwd_dkdv": 8.0 * w.d * n_unmasked,
+                              "bwd_dq": 6.0 * w.d * n_unmasked}
+        for ev_f, ev_b in evs:
+            for e in list(ev_f) + list(ev_b):
+                hip.hipEventDestroy(e)
+    return res
+
+
+def cpu_baseline(w, orc, workloads, budget_rows):
+    """The fp64 oracle, as it stands, timed on the host on a bounded sample of
+    the same workload: the full forward+backward work of `budget_rows` query
+    rows of head 0 (every key column), in the metric's unit."""
+    import threadpoolctl
+    bits = workloads.make_tensors(w.seed, 1, 1, w.N, w.d)     # one head's worth of the same recipe
+    arrs = [workloads.bf16_bits_to_f32(bits[n][0, 0]).astype(np.float64) for n in ("q", "k", "v", "dout")]
+    vec = w.vectors[0]
+    rows_total = min(budget_rows, w.N)
+    r_start = (w.N - rows_total) // 2
+    allowed = orc.allowed_keys_per_row(*vec)
+    t0 = time.perf_counter()
+    for r0 in range(r_start, r_start + rows_total, orc.ROW_CHUNK):
+        rows = np.arange(r0, min(r0 + orc.ROW_CHUNK, r_start + rows_total))
+        orc.backward_row_block(*arrs, *vec, w.scale, rows)
+    secs = time.perf_counter() - t0
+    unmasked = int(allowed[r_start:r_start + rows_total].sum())
+    flop = 14.0 * w.d * unmasked
+    threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+    return {"value": flop / secs / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp64 oracle forward+backward of {rows_total} query rows x all {w.N} keys of one head of "
+                      f"workload {w.name} ({secs:.1f} s; dense work, unmasked FLOPs counted)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, help="1, 2, 3, 4a, 4b or 5")
+    ap.add_argument("--others", default="2,3,4a,4b", help="extra workloads reported in `other_workloads` ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (batch x heads is the sharding axis; see DESIGN.md); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2410_01359_amd as fm
+    import workloads
+    from oracle import flashmask_oracle as orc      # FLOP counters and the cpu_baseline leg only
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    fm.load_library()
+    hip = hip_runtime()
+
+    main_res = run_workload(args.workload, args.steps, args.warmup, torch, fm, orc, workloads, hip, True)
+    w = main_res.pop("workload_obj")
+    others = []
+    for name in [x for x in args.others.split(",") if x and x != args.workload]:
+        r = run_workload(name, max(3, args.steps // 2), 2, torch, fm, orc, workloads, hip, True)
+        r.pop("workload_obj")
+        others.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                       if k in ("workload", "ms_per_step", "tflops", "block_sparsity", "fwd_ms", "bwd_ms")})
+        torch.cuda.empty_cache()
+
+    st = main_res["stage_ms"]
+    dominant = max(("fwd_tiles", "bwd_dkdv", "bwd_dq"), key=lambda k: st[k])
+    achieved = main_res["kernel_flop"][dominant] / st[dominant] / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{args.workload}:{dominant}")
+        except Exception:
+            traffic = None
+    line = {
+        "metric": "fwd+bwd TFLOPs/s (unmasked FLOPs) on 1 MI355X",
+        "value": round(main_res["tflops"], 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "pct_of_bf16_mfma_peak": round(100.0 * main_res["tflops"] / PEAK_BF16_TFLOPS, 2),
+        "config": {"workload": f"config {w.name}: {w.mask_kind} mask, B={w.B}, H={w.H}, N={w.N}, d={w.d}, bf16, "
+                               f"forward+backward, scale=1/sqrt(d)",
+                   "block_sparsity_128": round(main_res["block_sparsity"], 4),
+                   "unmasked_tflop_per_step": round(main_res["unmasked_tflop"], 4),
+                   "tile_tflop_per_step": round(main_res["tile_tflop"], 4),
+                   "fwd_ms": round(main_res["fwd_ms"], 4), "bwd_ms": round(main_res["bwd_ms"], 4),
+                   "stage_ms": {k: round(v, 4) for k, v in st.items()}},
+        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+        "other_workloads": others,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, orc, workloads, args.cpu_rows)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -148,6 +148,19 @@ const char* flashmask_strerror(int code);
 /* Text of the last HIP error behind an FM_ERR_HIP on this thread ("" if none). */
 const char* flashmask_last_hip_error(void);
 
+/*
+ * Measurement aid (not part of the paper's method): register `count` HOST
+ * handles of already-created hipEvent_t objects.  While registered, every
+ * flashmask_fwd / flashmask_bwd call records them on its stream between its
+ * internal launches, so a benchmark can time one kernel inside the call:
+ *   forward : [0] entry, [1] after preprocessing + launch order, [2] after the tile loop
+ *   backward: [0] entry, [1] after preprocessing + launch orders, [2] after the
+ *             D pre-pass, [3] after the dK/dV loop, [4] after the dQ loop
+ * The array must stay valid until cleared with (NULL, 0).  Process-global and
+ * not thread-safe; entries that are NULL or beyond `count` are skipped.
+ */
+int flashmask_profile_events(void** events, int count);
+
 #ifdef __cplusplus
 }
 #endif

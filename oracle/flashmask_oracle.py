@@ -139,29 +139,38 @@ def probabilities(q, k, lts, lte, uts, ute, scale):
 # --------------------------------------------------------------------------
 # Backward (Algorithm 2, written densely)
 # --------------------------------------------------------------------------
-def backward(q, k, v, dout, lts, lte, uts, ute, scale):
-    """dq, dk, dv (and out, lse) for one (batch, head); all [N,d] / [N]."""
+def backward_row_block(q, k, v, dout, lts, lte, uts, ute, scale, rows):
+    """Everything Algorithm 2 derives from the listed query rows: their out,
+    lse and dq, and the amounts they add to dk and dv (full [N,d] arrays)."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     dout = np.asarray(dout, dtype=np.float64)
-    n, d = q.shape
-    dq = np.zeros((n, d)); dk = np.zeros((n, d)); dv = np.zeros((n, v.shape[1]))
-    out = np.zeros((n, v.shape[1])); lse = np.zeros(n)
+    r = np.asarray(rows, dtype=np.int64)
+    masked = expand_mask(lts, lte, uts, ute, r)
+    p, lse = _softmax_rows(q[r], k, masked, scale)
+    out = p @ v
+    do = dout[r]
+    dv_part = p.T @ do
+    dp = do @ v.T
+    big_d = (do * out).sum(axis=1)
+    ds = p * (dp - big_d[:, None])
+    dq = scale * (ds @ k)
+    dk_part = scale * (ds.T @ q[r])
+    return dq, dk_part, dv_part, out, lse
+
+
+def backward(q, k, v, dout, lts, lte, uts, ute, scale):
+    """dq, dk, dv (and out, lse) for one (batch, head); all [N,d] / [N]."""
+    n, d = np.asarray(q).shape
+    dv_cols = np.asarray(v).shape[1]
+    dq = np.zeros((n, d)); dk = np.zeros((n, d)); dv = np.zeros((n, dv_cols))
+    out = np.zeros((n, dv_cols)); lse = np.zeros(n)
     for r0 in range(0, n, ROW_CHUNK):
         r = np.arange(r0, min(r0 + ROW_CHUNK, n))
-        masked = expand_mask(lts, lte, uts, ute, r)
-        p, l = _softmax_rows(q[r], k, masked, scale)
-        o = p @ v
-        do = dout[r]
-        dv += p.T @ do
-        dp = do @ v.T
-        big_d = (do * o).sum(axis=1)
-        ds = p * (dp - big_d[:, None])
-        dq[r] = scale * (ds @ k)
-        dk += scale * (ds.T @ q[r])
-        out[r] = o
-        lse[r] = l
+        dq[r], dk_part, dv_part, out[r], lse[r] = backward_row_block(q, k, v, dout, lts, lte, uts, ute, scale, r)
+        dk += dk_part
+        dv += dv_part
     return dq, dk, dv, out, lse
 
 

@@ -52,6 +52,8 @@ def load_library() -> ctypes.CDLL:
     lib.flashmask_strerror.argtypes = [i]
     lib.flashmask_last_hip_error.restype = ctypes.c_char_p
     lib.flashmask_last_hip_error.argtypes = []
+    lib.flashmask_profile_events.restype = i
+    lib.flashmask_profile_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), i]
     _LIB = lib
     return lib
 

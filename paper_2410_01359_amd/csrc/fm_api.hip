@@ -16,6 +16,13 @@ int hip_fail(hipError_t e) {
   return FM_ERR_HIP;
 }
 
+// Optional measurement aid: events recorded between the internal launches.
+hipEvent_t* g_prof_events = nullptr;
+int g_prof_count = 0;
+inline void mark(int idx, hipStream_t stream) {
+  if (g_prof_events && idx < g_prof_count && g_prof_events[idx]) (void)hipEventRecord(g_prof_events[idx], stream);
+}
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -60,6 +67,13 @@ const char* flashmask_strerror(int code) {
 }
 
 const char* flashmask_last_hip_error(void) { return g_hip_error; }
+
+int flashmask_profile_events(void** events, int count) {
+  if (count < 0 || (count > 0 && !events)) return FM_ERR_ARG;
+  g_prof_events = count ? (hipEvent_t*)events : nullptr;
+  g_prof_count = count;
+  return FM_OK;
+}
 
 int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c) {
   if (!block_r || !block_c) return FM_ERR_NULL;
@@ -116,10 +130,12 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   int* minmax = (int*)(ws + sp.minmax);
   int* work = (int*)(ws + sp.work);
   int* order = (int*)(ws + sp.order);
+  mark(0, stream);
   hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_FWD_BC, minmax, stream);
   if (e != hipSuccess) return hip_fail(e);
   e = fm_launch_row_order(minmax, B, H, N, FM_FWD_BR, FM_FWD_BC, work, order, stream);
   if (e != hipSuccess) return hip_fail(e);
+  mark(1, stream);
   FmFwdArgs a;
   a.q = q; a.k = k; a.v = v;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
@@ -128,7 +144,9 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.slots = fm_order_slots(B * H * (N / FM_FWD_BR));
   e = fm_launch_fwd(a, stream);
-  return e == hipSuccess ? FM_OK : hip_fail(e);
+  if (e != hipSuccess) return hip_fail(e);
+  mark(2, stream);
+  return FM_OK;
 }
 
 int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse, const void* dout,
@@ -157,6 +175,7 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.slots_dq = fm_order_slots(B * H * (N / FM_DQ_BR));
   a.slots_dkdv = fm_order_slots(B * H * (N / FM_DKDV_BC));
+  mark(0, stream);
   hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
   e = fm_launch_row_order(a.minmax_dq, B, H, N, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.order), stream);
@@ -166,12 +185,17 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   e = fm_launch_col_order(a.minmax_dkdv, B, H, N, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
                           (int*)(ws + skv.order), stream);
   if (e != hipSuccess) return hip_fail(e);
+  mark(1, stream);
   e = fm_launch_dvec(a, stream);
   if (e != hipSuccess) return hip_fail(e);
+  mark(2, stream);
   e = fm_launch_bwd_dkdv(a, stream);
   if (e != hipSuccess) return hip_fail(e);
+  mark(3, stream);
   e = fm_launch_bwd_dq(a, stream);
-  return e == hipSuccess ? FM_OK : hip_fail(e);
+  if (e != hipSuccess) return hip_fail(e);
+  mark(4, stream);
+  return FM_OK;
 }
 
 }  // extern "C"
