@@ -45,7 +45,7 @@ enum {
   FM_ERR_ALIGN = -3,     /* a tensor pointer is not 16-byte aligned */
   FM_ERR_WORKSPACE = -4, /* workspace is NULL or smaller than flashmask_workspace_bytes() */
   FM_ERR_HIP = -5,       /* a kernel launch failed; see flashmask_last_hip_error() */
-  FM_ERR_ARG = -6        /* unknown pass id or other bad scalar argument */
+  FM_ERR_ARG = -6        /* unknown pass id, scale <= 0 or not finite */
 };
 
 /* Pass ids for flashmask_workspace_bytes / flashmask_tile_shape. */
@@ -75,7 +75,8 @@ enum {
  *
  *   q, k, v        in   bf16 [B,H,N,d]
  *   lts..ute       in   int32 [B,N]
- *   scale          in   multiplies Q K^T (1/sqrt(d) in the paper's Equation 1)
+ *   scale          in   multiplies Q K^T (1/sqrt(d) in the paper's Equation 1); must be
+ *                       positive and finite (FM_ERR_ARG otherwise)
  *   out            out  bf16 [B,H,N,d]
  *   lse            out  fp32 [B,H,N]
  *   workspace      scratch of at least flashmask_workspace_bytes(FM_PASS_FWD, ...)

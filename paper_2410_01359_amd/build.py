@@ -13,6 +13,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-value",
+    # the tile loops are written as fully unrolled step sequences (#pragma unroll over
+    # compile-time schedules); the default size cap on pragma-driven unrolling is too small
+    "-mllvm", "-pragma-unroll-threshold=1000000",
 ]
 
 

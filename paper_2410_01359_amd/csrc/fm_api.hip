@@ -61,7 +61,7 @@ const char* flashmask_strerror(int code) {
     case FM_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
     case FM_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
     case FM_ERR_HIP: return "HIP launch failed (see flashmask_last_hip_error)";
-    case FM_ERR_ARG: return "bad scalar argument";
+    case FM_ERR_ARG: return "bad scalar argument (unknown pass id, or scale not a positive finite number)";
     default: return "unknown flashmask error code";
   }
 }
@@ -92,7 +92,7 @@ size_t flashmask_workspace_bytes(int pass, int B, int H, int N, int d) {
   if (pass == FM_PASS_BWD) {
     const PassSpace dq = pass_space(B, H, N, FM_DQ_BR, FM_DQ_BC, true, 0);
     const PassSpace kv = pass_space(B, H, N, FM_DKDV_BR, FM_DKDV_BC, false, dq.total);
-    return kv.total + align_up((size_t)B * H * N * 4, 256);  // + D vector
+    return kv.total + 2 * align_up((size_t)B * H * N * 4, 256);  // + D vector + log2-domain lse
   }
   return 0;
 }
@@ -119,6 +119,7 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
                   int d, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!q || !k || !v || !lts || !lte || !uts || !ute || !out || !lse) return FM_ERR_NULL;
   if (int rc = check_shape(B, H, N, d)) return rc;
+  if (!(scale > 0.f) || !(scale < 3.0e38f)) return FM_ERR_ARG;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lts) || misaligned(lte) ||
       misaligned(uts) || misaligned(ute) || misaligned(lse))
     return FM_ERR_ALIGN;
@@ -155,6 +156,7 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
                   void* hip_stream) {
   if (!q || !k || !v || !out || !lse || !dout || !lts || !lte || !uts || !ute || !dq || !dk || !dv) return FM_ERR_NULL;
   if (int rc = check_shape(B, H, N, d)) return rc;
+  if (!(scale > 0.f) || !(scale < 3.0e38f)) return FM_ERR_ARG;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dout) || misaligned(dq) ||
       misaligned(dk) || misaligned(dv) || misaligned(lts) || misaligned(lte) || misaligned(uts) || misaligned(ute) ||
       misaligned(lse))
@@ -171,6 +173,7 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   a.minmax_dq = (int*)(ws + sq.minmax); a.order_dq = (int*)(ws + sq.order);
   a.minmax_dkdv = (int*)(ws + skv.minmax); a.order_dkdv = (int*)(ws + skv.order);
   a.dvec = (float*)(ws + skv.total);
+  a.lse2 = (float*)(ws + skv.total + align_up((size_t)B * H * N * 4, 256));
   a.dq = dq; a.dk = dk; a.dv = dv; a.scale = scale;
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.slots_dq = fm_order_slots(B * H * (N / FM_DQ_BR));

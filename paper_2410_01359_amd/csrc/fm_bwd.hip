@@ -17,11 +17,13 @@
 namespace fm {
 
 // ---------------------------------------------------------------------------
-// D pre-pass.  One row per 16 (d = 128) or 8 (d = 64) lanes, 16 bytes per lane.
+// D pre-pass (plus the log2-domain copy of lse the tile loops use).  One row per
+// 16 (d = 128) or 8 (d = 64) lanes, 16 bytes per lane.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
-                                                   float* __restrict__ dvec, long long rows) {
+                                                   const float* __restrict__ lse, float* __restrict__ dvec,
+                                                   float* __restrict__ lse2, long long rows) {
   constexpr int LPR = D / 8;  // lanes per row
   const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long row = gid / LPR;
@@ -35,7 +37,13 @@ __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ ou
   }
 #pragma unroll
   for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (row < rows && part == 0) dvec[row] = acc;
+  if (row < rows && part == 0) {
+    dvec[row] = acc;
+    // lse for the backward's exponent: log2 domain, and +inf for a row with no
+    // visible key (lse = -inf) so that exp2(s - lse2) is exactly 0 there
+    const float l = lse[row];
+    lse2[row] = (l == -INFINITY) ? INFINITY : l * kLog2e;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -45,16 +53,15 @@ template <int D>
 struct DqCfg {
   static constexpr int KT = FM_DQ_BC;
   static constexpr int BR = FM_DQ_BR;
-  static constexpr int RS = D * 2 + 16;  // K and V row stride in LDS (bytes)
-  static constexpr int K_BYTES = KT * RS;
-  static constexpr int V_BYTES = KT * RS;
+  using L = TileLayout<D>;
+  static constexpr int K_BYTES = KT * L::RS;
+  static constexpr int V_BYTES = KT * L::RS;
   static constexpr int BND_BYTES = 4 * KT * 4;
   static constexpr int STAGE = K_BYTES + V_BYTES + BND_BYTES;
   static constexpr int LIST_CAP = 1024;
   static constexpr int CNT_OFF = LIST_CAP * 4;
   static constexpr int STAGE_OFF = CNT_OFF + 64;
   static constexpr int LDS_BYTES = STAGE_OFF + 2 * STAGE;
-  static constexpr int NCH = KT * D / 8 / 256;
 };
 
 template <int D>
@@ -80,8 +87,17 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   const __bf16* vp = (const __bf16*)a.v + (size_t)bh * N * D;
   const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * N * D;
   const int* table = a.minmax_dq + (size_t)b * 8 * t_c;
-  const int *bvec0 = a.lts + (size_t)b * N, *bvec1 = a.lte + (size_t)b * N, *bvec2 = a.uts + (size_t)b * N,
-            *bvec3 = a.ute + (size_t)b * N;
+  // lanes of wave 0 copy the four bound slices of a partially masked tile
+  const int* my_bvec;
+  {
+    const int which = lane >> 4;
+    const int* p = a.lts;
+    if (which == 1) p = a.lte;
+    if (which == 2) p = a.uts;
+    if (which == 3) p = a.ute;
+    my_bvec = p + (size_t)b * N + (lane & 15) * 4;
+  }
+  const int lane_src = async_src_offset<D>(wave, lane);
 
   bf16x8 qreg[NKK], doreg[NKK];
 #pragma unroll
@@ -89,9 +105,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     qreg[kk] = *(const bf16x8*)(qp + (size_t)row * D + kk * 16 + 8 * g);
     doreg[kk] = *(const bf16x8*)(dop + (size_t)row * D + kk * 16 + 8 * g);
   }
-  // lse in the log2 domain; a row with no visible key (lse = -inf) must give P = 0
-  const float lse_raw = a.lse[(size_t)bh * N + row];
-  const float lse2 = (lse_raw == -INFINITY) ? INFINITY : lse_raw * kLog2e;
+  // lse in the log2 domain (+inf for a row with no visible key, so that P = 0 there)
+  const float lse2 = a.lse2[(size_t)bh * N + row];
   const float dsum = a.dvec[(size_t)bh * N + row];
 
   f32x16 dqacc[NDB];
@@ -103,38 +118,21 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   int* list = (int*)smem;
   int* wave_cnt = (int*)(smem + C::CNT_OFF);
   const float sc = a.scale * kLog2e;
+  // lane-dependent LDS offsets inside a tile (row block 0, first column group)
+  const int i16 = lane & 15, half = (lane >> 4) & 1;
+  const int a_base = C::L::off(c, 16 * g);
+  const int t_base0 = C::L::off(4 * g + (i16 >> 2), (16 * half + 4 * (i16 & 3)) * 2);
+  const int t_base1 = C::L::off(4 * g + (i16 >> 2) + 8, (16 * half + 4 * (i16 & 3)) * 2);
 
-  u32x4 kst[C::NCH], vst[C::NCH], bst[4];
-#define FM_ISSUE_LOADS(ENTRY)                                               \
-  {                                                                         \
-    const int j_ = (ENTRY) & 0xFFFFFF;                                      \
-    _Pragma("unroll") for (int s = 0; s < C::NCH; ++s) {                    \
-      const int ch = tid + 256 * s;                                         \
-      const int rw = ch / (D / 8), col = ch % (D / 8);                      \
-      const size_t off = (size_t)(j_ * KT + rw) * D + col * 8;              \
-      kst[s] = ldg16(kp + off);                                             \
-      vst[s] = ldg16(vp + off);                                             \
-    }                                                                       \
-    if ((((ENTRY) >> 24) & T_PARTIAL) && tid < KT / 4) {                    \
-      bst[0] = ldg16(bvec0 + j_ * KT + tid * 4);                            \
-      bst[1] = ldg16(bvec1 + j_ * KT + tid * 4);                            \
-      bst[2] = ldg16(bvec2 + j_ * KT + tid * 4);                            \
-      bst[3] = ldg16(bvec3 + j_ * KT + tid * 4);                            \
-    }                                                                       \
-  }
-#define FM_STORE_STAGE(ENTRY, BUF)                                          \
-  {                                                                         \
-    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                     \
-    _Pragma("unroll") for (int s = 0; s < C::NCH; ++s) {                    \
-      const int ch = tid + 256 * s;                                         \
-      const int rw = ch / (D / 8), col = ch % (D / 8);                      \
-      *(u32x4*)(st_ + rw * C::RS + col * 16) = kst[s];                      \
-      *(u32x4*)(st_ + C::K_BYTES + rw * C::RS + col * 16) = vst[s];         \
-    }                                                                       \
-    if ((((ENTRY) >> 24) & T_PARTIAL) && tid < KT / 4) {                    \
-      _Pragma("unroll") for (int v_ = 0; v_ < 4; ++v_)                      \
-          *(u32x4*)(st_ + C::K_BYTES + C::V_BYTES + v_ * KT * 4 + tid * 16) = bst[v_]; \
-    }                                                                       \
+#define FM_LOAD_TILE(ENTRY, BUF)                                                               \
+  {                                                                                            \
+    const int j_ = (ENTRY) & 0xFFFFFF;                                                         \
+    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
+    tile_load_async<D, KT>(kp + (size_t)j_ * KT * D, lane_src, st_, wave);                     \
+    tile_load_async<D, KT>(vp + (size_t)j_ * KT * D, lane_src, st_ + C::K_BYTES, wave);        \
+    if ((((ENTRY) >> 24) & T_PARTIAL) && wave == 0)                                            \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(my_bvec + j_ * KT), \
+                                       (FM_LDS void*)(st_ + C::K_BYTES + C::V_BYTES), 16, 0, 0); \
   }
 
   for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
@@ -142,15 +140,14 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
                                              list, wave_cnt);
     if (n_live == 0) continue;
     const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
-    FM_ISSUE_LOADS(first_entry);
-    FM_STORE_STAGE(first_entry, 0);
+    FM_LOAD_TILE(first_entry, 0);
     __syncthreads();
 
     for (int t = 0; t < n_live; ++t) {
       const int entry = __builtin_amdgcn_readfirstlane(list[t]);
       const int j = entry & 0xFFFFFF;
       const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
-      if (t + 1 < n_live) FM_ISSUE_LOADS(next_entry);
+      if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
 
       const char* st = smem + C::STAGE_OFF + (t & 1) * C::STAGE;
       const char* ks = st;
@@ -159,7 +156,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 
       const int wcls = classify_tile(qw0, qw0 + 32, load_minmax(table, t_c, j));
       if (wcls != T_FULLY) {
-        const int i16 = lane & 15, half = (lane >> 4) & 1;
+        const int a_b = opaque(a_base), t_b0 = opaque(t_base0), t_b1 = opaque(t_base1);
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
           f32x16 sacc, dpacc;
@@ -171,13 +168,12 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
           // S^T = K Q^T and dP^T = V dO^T for 32 keys x 32 queries
 #pragma unroll
           for (int kk = 0; kk < NKK; ++kk) {
-            const bf16x8 ka = *(const bf16x8*)(ks + (kb * 32 + c) * C::RS + (kk * 16 + 8 * g) * 2);
+            const int ao = C::L::add_col(a_b, kk * 32);
+            const bf16x8 ka = *(const bf16x8*)(ks + kb * 32 * C::L::RS + ao);
             sacc = mfma32(ka, qreg[kk], sacc);
-            const bf16x8 va = *(const bf16x8*)(vs + (kb * 32 + c) * C::RS + (kk * 16 + 8 * g) * 2);
+            const bf16x8 va = *(const bf16x8*)(vs + kb * 32 * C::L::RS + ao);
             dpacc = mfma32(va, doreg[kk], dpacc);
           }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[r] *= sc;
           if (wcls & T_PARTIAL) {
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
@@ -196,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
           // P = exp(S - L), dS = P o (dP - D)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(sacc[r] - lse2);
+            const float p = fast_exp2(__builtin_fmaf(sacc[r], sc, -lse2));
             sacc[r] = p * (dpacc[r] - dsum);
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -206,12 +202,11 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
             bf16x8 dsb;
 #pragma unroll
             for (int e = 0; e < 8; ++e) dsb[e] = (__bf16)sacc[8 * h + e];
-            const int row0 = kb * 32 + 16 * h + 4 * g + (i16 >> 2);
+            const char* krow = ks + (kb * 32 + 16 * h) * C::L::RS;
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-              const int col = db * 32 + 16 * half + 4 * (i16 & 3);
-              const bf16x4 lo = lds_read_tr16(ks + row0 * C::RS + col * 2);
-              const bf16x4 hi = lds_read_tr16(ks + (row0 + 8) * C::RS + col * 2);
+              const bf16x4 lo = lds_read_tr16(krow + C::L::add_col(t_b0, db * 64));
+              const bf16x4 hi = lds_read_tr16(krow + C::L::add_col(t_b1, db * 64));
               dqacc[db] = mfma32(cat4(lo, hi), dsb, dqacc[db]);
             }
           }
@@ -219,12 +214,10 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
         }
       }
 
-      if (t + 1 < n_live) FM_STORE_STAGE(next_entry, (t + 1) & 1);
       __syncthreads();
     }
   }
-#undef FM_ISSUE_LOADS
-#undef FM_STORE_STAGE
+#undef FM_LOAD_TILE
 
   __bf16* dqp = (__bf16*)a.dq + (size_t)bh * N * D;
 #pragma unroll
@@ -245,27 +238,174 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 // NOT transposed here (S = Q K^T): every lane then holds one KEY column, so the
 // four bounds of that key sit in four registers for the whole kernel and P^T,
 // dS^T are already A operands of dV += P^T dO and dK += dS^T Q.
+//
+// One wave per SIMD (the accumulators alone take 128 registers), so the
+// overlap of matrix and vector work is arranged inside the wave: a 64-row tile
+// is two 32-row blocks, and the instruction stream is
+//   S0,dP0 | S1,dP1 with the exp/dS arithmetic of block 0 between the MFMAs |
+//   dV,dK of block 0 with the arithmetic of block 1 between the MFMAs | dV,dK of block 1
+// with every LDS operand fetched a fixed number of steps ahead of its MFMA.
+// Scheduling fences pin that order.
 // ---------------------------------------------------------------------------
 template <int D>
 struct DkdvCfg {
   static constexpr int QT = FM_DKDV_BR;    // query rows per step
   static constexpr int BC = FM_DKDV_BC;    // keys per workgroup
-  static constexpr int RS = D * 2 + 16;    // Q and dO row stride in LDS (bytes)
-  static constexpr int Q_BYTES = QT * RS;
-  static constexpr int DO_BYTES = QT * RS;
-  static constexpr int VEC_BYTES = 2 * QT * 4;  // lse (log2 domain) and D of the rows
+  using L = TileLayout<D>;
+  static constexpr int Q_BYTES = QT * L::RS;
+  static constexpr int DO_BYTES = QT * L::RS;
+  static constexpr int VEC_BYTES = 2 * QT * 4;  // lse (log2 domain, +inf for dead rows) and D of the rows
   static constexpr int STAGE = Q_BYTES + DO_BYTES + VEC_BYTES;
   static constexpr int LIST_CAP = 2048;
   static constexpr int CNT_OFF = LIST_CAP * 4;
   static constexpr int STAGE_OFF = CNT_OFF + 64;
-  static constexpr int LDS_BYTES = STAGE_OFF + 2 * STAGE;
-  static constexpr int NCH = QT * D / 8 / 256;
+  // One workgroup per CU: a tile's math takes about a microsecond, less than a
+  // trip to L2/HBM, so tiles are copied three steps ahead into a ring of four.
+  static constexpr int NSTAGE = 4;
+  static constexpr int LDS_BYTES = STAGE_OFF + NSTAGE * STAGE;
+  // async copy instructions one wave issues per tile (wave 0 issues one more, for lse / D)
+  static constexpr int COPIES = 2 * (QT / (64 / L::CPR) / 4);
 };
+
+// Wait until at most `tiles_behind` later tile copies of this wave are still in
+// flight (the copies complete in issue order), i.e. until the tile issued
+// before them has landed in LDS.
+template <int COPIES>
+__device__ __forceinline__ void wait_tile_landed(int tiles_behind, bool extra_copy) {
+  if (extra_copy) {
+    if (tiles_behind >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (COPIES + 1)) : "memory");
+    else if (tiles_behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(COPIES + 1) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  } else {
+    if (tiles_behind >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * COPIES) : "memory");
+    else if (tiles_behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(COPIES) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+}
+
+// Workgroup barrier without the memory fence of __syncthreads() (which would
+// drain every outstanding async copy): the caller has already waited for the
+// copies that must be visible, and all LDS reads of the tile being replaced
+// were consumed by MFMAs before the wave got here.
+__device__ __forceinline__ void barrier_nofence() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+#define FM_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// exp / dS arithmetic of elements [e0, e0 + cnt) of one 32x32 block held in the
+// MFMA output layout: register r is query row 8*(r/4) + 4*g + r%4 of the block.
+template <bool MASKED>
+__device__ __forceinline__ void dkdv_elems(f32x16& s, f32x16& dp, const f32x4 (&l4)[4], const f32x4 (&d4)[4], int e0,
+                                           int cnt, int row_base /* r0 + 32*qb + 4*g */, float sc, int b_lts,
+                                           int b_lte, int b_uts, int b_ute) {
+#pragma unroll
+  for (int r = e0; r < e0 + cnt; ++r) {
+    float x = s[r];
+    if (MASKED) {
+      const int qrow = row_base + 8 * (r >> 2) + (r & 3);
+      const bool masked = ((qrow >= b_lts) & (qrow < b_lte)) | ((qrow >= b_uts) & (qrow < b_ute));
+      if (masked) x = -INFINITY;
+    }
+    const float p = fast_exp2(__builtin_fmaf(x, sc, -l4[r >> 2][r & 3]));
+    s[r] = p;
+    dp[r] = p * (dp[r] - d4[r >> 2][r & 3]);
+  }
+}
+
+// One 64-row tile = two 32-row blocks.  The tile's 8*NKK MFMAs form one stream
+//   [S0 | dP0 | S1 | dP1 | dV,dK of block 0 | dV,dK of block 1]      (NKK = D/16 MFMAs per bar, 2*NKK for dV,dK)
+// each taking one operand from LDS (a 128-bit row read for the first four
+// groups, a transpose read for the rest) that is fetched RD steps ahead into a
+// small register ring.  The exp / dS arithmetic of block 0 is spread over the
+// steps of S1 and dP1, that of block 1 over the dV,dK steps of block 0, so the
+// vector work always has matrix work in flight beside it.
+template <int D, bool MASKED>
+__device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const float* lse_s, const float* dv_s,
+                                          const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
+                                          f32x16 (&dkacc)[D / 32], f32x16 (&dvacc)[D / 32], int a_base, int t_base0,
+                                          int t_base1, int r0, int g, float sc, int b_lts, int b_lte, int b_uts,
+                                          int b_ute) {
+  using L = TileLayout<D>;
+  constexpr int NKK = D / 16, NDB = D / 32;
+  constexpr int NST = 2 * NKK;     // MFMAs per block and product pair
+  constexpr int EPS = 16 / NST;    // elements handled next to one MFMA (D = 128: 1, D = 64: 2)
+  constexpr int NX = 4 * NST;      // MFMAs per tile
+  constexpr int RD = 4;            // operand fetch distance (steps)
+  const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+  // LDS operand of step x
+  auto operand = [&](int x) __attribute__((always_inline)) {
+    if (x < 2 * NST) {             // row reads: Q or dO rows of block x / NST as MFMA A operand
+      const int qb = x / NST, kk = x % NKK;
+      const char* tile = ((x / NKK) & 1) ? dos : qs;
+      return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, kk * 32));
+    }
+    // transpose reads: dO (even step, dV) or Q (odd step, dK) as MFMA B operand
+    const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
+    const char* tile = (u & 1) ? qs : dos;
+    const char* rowp = tile + (qb * 32 + 16 * h) * L::RS;
+    return cat4(lds_read_tr16(rowp + L::add_col(t_base0, db * 64)), lds_read_tr16(rowp + L::add_col(t_base1, db * 64)));
+  };
+
+  bf16x8 op[RD];
+  f32x16 sb[2], pb[2];             // S then P, dP then dS, of the two blocks
+  bf16x8 pa[2][2], dsa[2][2];      // bf16 P^T and dS^T, [block][16-row half]
+  f32x4 l4[2][4], d4[2][4];        // lse (log2 domain) and D of the blocks' rows, fetched one group of 4 rows ahead
+  auto vec_group = [&](int qb, int grp) __attribute__((always_inline)) {
+    l4[qb][grp] = *(const f32x4*)(lse_s + qb * 32 + 8 * grp + 4 * g);
+    d4[qb][grp] = *(const f32x4*)(dv_s + qb * 32 + 8 * grp + 4 * g);
+  };
+
+#pragma unroll
+  for (int x = 0; x < RD; ++x) op[x] = operand(x);
+  FM_FENCE();
+#pragma unroll
+  for (int x = 0; x < NX; ++x) {
+    // --- the MFMA of this step
+    if (x < 2 * NST) {
+      const int qb = x / NST, kk = x % NKK;
+      if (((x / NKK) & 1) == 0)
+        sb[qb] = mfma32(op[x % RD], kreg[kk], kk == 0 ? zero : sb[qb]);
+      else
+        pb[qb] = mfma32(op[x % RD], vreg[kk], kk == 0 ? zero : pb[qb]);
+    } else {
+      const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
+      if (u & 1)
+        dkacc[db] = mfma32(dsa[qb][h], op[x % RD], dkacc[db]);
+      else
+        dvacc[db] = mfma32(pa[qb][h], op[x % RD], dvacc[db]);
+    }
+    // --- fetch the operand of step x + RD
+    if (x + RD < NX) op[x % RD] = operand(x + RD);
+    // --- vector work riding along: block 0 during steps [NST, 2 NST), block 1 during [2 NST, 3 NST)
+    if (x == NST - 1) vec_group(0, 0);
+    if (x == 2 * NST - 1) vec_group(1, 0);
+    if (x >= NST && x < 3 * NST) {
+      const int qb = (x - NST) / NST, e0 = ((x - NST) % NST) * EPS;
+      if (e0 % 4 == 0 && e0 / 4 + 1 < 4) vec_group(qb, e0 / 4 + 1);
+      dkdv_elems<MASKED>(sb[qb], pb[qb], l4[qb], d4[qb], e0, EPS, r0 + 32 * qb + 4 * g, sc, b_lts, b_lte, b_uts, b_ute);
+      if (e0 + EPS == 16) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            pa[qb][hh][e] = (__bf16)sb[qb][8 * hh + e];
+            dsa[qb][hh][e] = (__bf16)pb[qb][8 * hh + e];
+          }
+      }
+    }
+    FM_FENCE();
+  }
+}
 
 template <int D>
 __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   using C = DkdvCfg<D>;
-  constexpr int QT = C::QT, NQB = QT / 32, NDB = D / 32, NKK = D / 16;
+  constexpr int QT = C::QT, NDB = D / 32, NKK = D / 16;
+  static_assert(QT == 64, "the tile loop is written for two 32-row blocks per tile");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int unit = a.order_dkdv[blockIdx.x];
@@ -284,7 +424,7 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const __bf16* kp = (const __bf16*)a.k + (size_t)bh * N * D;
   const __bf16* vp = (const __bf16*)a.v + (size_t)bh * N * D;
   const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * N * D;
-  const float* lsep = a.lse + (size_t)bh * N;
+  const float* lsep = a.lse2 + (size_t)bh * N;
   const float* dvp = a.dvec + (size_t)bh * N;
 
   // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T)
@@ -328,53 +468,49 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   int* list = (int*)smem;
   int* wave_cnt = (int*)(smem + C::CNT_OFF);
   const float sc = a.scale * kLog2e;
+  // lane-dependent LDS offsets inside a tile (row block 0, first column group)
+  const int i16 = lane & 15, half = (lane >> 4) & 1;
+  const int a_base = C::L::off(c, 16 * g);
+  const int t_base0 = C::L::off(4 * g + (i16 >> 2), (16 * half + 4 * (i16 & 3)) * 2);
+  const int t_base1 = C::L::off(4 * g + (i16 >> 2) + 8, (16 * half + 4 * (i16 & 3)) * 2);
+  const int lane_src = async_src_offset<D>(wave, lane);
+  // wave 0 also copies the tile's lse and D slices: lanes 0-15 lse, lanes 16-31 D, 16 bytes each
+  const float* my_vec = ((lane & 16) ? dvp : lsep) + (lane & 15) * 4;
 
-  u32x4 qst[C::NCH], dost[C::NCH];
-  float vecst = 0.f;
-#define FM_ISSUE_LOADS(ENTRY)                                               \
-  {                                                                         \
-    const int i_ = (ENTRY) & 0xFFFFFF;                                      \
-    _Pragma("unroll") for (int s = 0; s < C::NCH; ++s) {                    \
-      const int ch = tid + 256 * s;                                         \
-      const int rw = ch / (D / 8), col = ch % (D / 8);                      \
-      const size_t off = (size_t)(i_ * QT + rw) * D + col * 8;              \
-      qst[s] = ldg16(qp + off);                                             \
-      dost[s] = ldg16(dop + off);                                           \
-    }                                                                       \
-    if (tid < QT) {                                                         \
-      const float x = lsep[i_ * QT + tid];                                  \
-      vecst = (x == -INFINITY) ? INFINITY : x * kLog2e;                     \
-    } else if (tid < 2 * QT) {                                              \
-      vecst = dvp[i_ * QT + tid - QT];                                      \
-    }                                                                       \
-  }
-#define FM_STORE_STAGE(BUF)                                                 \
-  {                                                                         \
-    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                     \
-    _Pragma("unroll") for (int s = 0; s < C::NCH; ++s) {                    \
-      const int ch = tid + 256 * s;                                         \
-      const int rw = ch / (D / 8), col = ch % (D / 8);                      \
-      *(u32x4*)(st_ + rw * C::RS + col * 16) = qst[s];                      \
-      *(u32x4*)(st_ + C::Q_BYTES + rw * C::RS + col * 16) = dost[s];        \
-    }                                                                       \
-    if (tid < 2 * QT) *(float*)(st_ + C::Q_BYTES + C::DO_BYTES + tid * 4) = vecst; \
+#define FM_LOAD_TILE(ENTRY, BUF)                                                                 \
+  {                                                                                              \
+    const int i_ = (ENTRY) & 0xFFFFFF;                                                           \
+    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                          \
+    tile_load_async<D, QT>(qp + (size_t)i_ * QT * D, lane_src, st_, wave);                       \
+    tile_load_async<D, QT>(dop + (size_t)i_ * QT * D, lane_src, st_ + C::Q_BYTES, wave);         \
+    if (wave == 0 && lane < 32)                                                                  \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(my_vec + i_ * QT), \
+                                       (FM_LDS void*)(st_ + C::Q_BYTES + C::DO_BYTES), 16, 0, 0); \
   }
 
   for (int chunk = 0; chunk < t_r; chunk += C::LIST_CAP) {
     const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, t_r), list, wave_cnt);
     if (n_live == 0) continue;
-    const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
-    FM_ISSUE_LOADS(first_entry);
-    FM_STORE_STAGE(0);
-    __syncthreads();
+    // prologue: copies of the first NSTAGE - 1 tiles
+#pragma unroll
+    for (int p = 0; p < C::NSTAGE - 1; ++p)
+      if (p < n_live) {
+        const int e = __builtin_amdgcn_readfirstlane(list[p]);
+        FM_LOAD_TILE(e, p);
+      }
 
     for (int t = 0; t < n_live; ++t) {
+      // tile t has landed once at most min(NSTAGE - 2, tiles after t) later copies are in flight
+      wait_tile_landed<C::COPIES>(min(C::NSTAGE - 2, n_live - 1 - t), wave == 0);
+      barrier_nofence();   // every wave's part of tile t is in LDS; every wave is done with tile t - 1
+      if (t + C::NSTAGE - 1 < n_live) {
+        const int e = __builtin_amdgcn_readfirstlane(list[t + C::NSTAGE - 1]);
+        FM_LOAD_TILE(e, (t + C::NSTAGE - 1) % C::NSTAGE);
+      }
       const int entry = __builtin_amdgcn_readfirstlane(list[t]);
       const int i_blk = entry & 0xFFFFFF;
-      const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
-      if (t + 1 < n_live) FM_ISSUE_LOADS(next_entry);
 
-      const char* st = smem + C::STAGE_OFF + (t & 1) * C::STAGE;
+      const char* st = smem + C::STAGE_OFF + (t % C::NSTAGE) * C::STAGE;
       const char* qs = st;
       const char* dos = st + C::Q_BYTES;
       const float* lse_s = (const float*)(st + C::Q_BYTES + C::DO_BYTES);
@@ -383,75 +519,17 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
 
       const int wcls = classify_tile(r0, min(r0 + QT, N), wmm);
       if (wcls != T_FULLY) {
-        const int i16 = lane & 15, half = (lane >> 4) & 1;
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          f32x16 sacc, dpacc;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            sacc[r] = 0.f;
-            dpacc[r] = 0.f;
-          }
-          // S = Q K^T, dP = dO V^T for 32 queries x 32 keys
-#pragma unroll
-          for (int kk = 0; kk < NKK; ++kk) {
-            const bf16x8 qa = *(const bf16x8*)(qs + (qb * 32 + c) * C::RS + (kk * 16 + 8 * g) * 2);
-            sacc = mfma32(qa, kreg[kk], sacc);
-            const bf16x8 da = *(const bf16x8*)(dos + (qb * 32 + c) * C::RS + (kk * 16 + 8 * g) * 2);
-            dpacc = mfma32(da, vreg[kk], dpacc);
-          }
-          // register r holds query row qb*32 + 8*(r/4) + 4*g + r%4 of this tile
-#pragma unroll
-          for (int rq = 0; rq < 4; ++rq) {
-            const int rl = qb * 32 + 8 * rq + 4 * g;
-            const f32x4 l4 = *(const f32x4*)(lse_s + rl);
-            const f32x4 d4 = *(const f32x4*)(dv_s + rl);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int r = rq * 4 + e;
-              const int qrow = r0 + rl + e;
-              float s = sacc[r] * sc;
-              if (wcls & T_PARTIAL) {
-                const bool masked = ((qrow >= b_lts) & (qrow < b_lte)) | ((qrow >= b_uts) & (qrow < b_ute));
-                if (masked) s = -INFINITY;
-              }
-              const float p = fast_exp2(s - l4[e]);
-              sacc[r] = p;
-              dpacc[r] = p * (dpacc[r] - d4[e]);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-          // dV += P^T dO, dK += dS^T Q
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            bf16x8 pa, dsa;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              pa[e] = (__bf16)sacc[8 * h + e];
-              dsa[e] = (__bf16)dpacc[8 * h + e];
-            }
-            const int row0 = qb * 32 + 16 * h + 4 * g + (i16 >> 2);
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-              const int col = db * 32 + 16 * half + 4 * (i16 & 3);
-              const bf16x4 dlo = lds_read_tr16(dos + row0 * C::RS + col * 2);
-              const bf16x4 dhi = lds_read_tr16(dos + (row0 + 8) * C::RS + col * 2);
-              dvacc[db] = mfma32(pa, cat4(dlo, dhi), dvacc[db]);
-              const bf16x4 qlo = lds_read_tr16(qs + row0 * C::RS + col * 2);
-              const bf16x4 qhi = lds_read_tr16(qs + (row0 + 8) * C::RS + col * 2);
-              dkacc[db] = mfma32(dsa, cat4(qlo, qhi), dkacc[db]);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
+        if (wcls & T_PARTIAL)
+          dkdv_tile<D, true>(qs, dos, lse_s, dv_s, kreg, vreg, dkacc, dvacc, a_base, t_base0, t_base1, r0, g, sc, b_lts,
+                             b_lte, b_uts, b_ute);
+        else
+          dkdv_tile<D, false>(qs, dos, lse_s, dv_s, kreg, vreg, dkacc, dvacc, a_base, t_base0, t_base1, r0, g, sc,
+                              b_lts, b_lte, b_uts, b_ute);
       }
-
-      if (t + 1 < n_live) FM_STORE_STAGE((t + 1) & 1);
-      __syncthreads();
     }
+    __syncthreads();   // the list and the ring are rebuilt by the next chunk
   }
-#undef FM_ISSUE_LOADS
-#undef FM_STORE_STAGE
+#undef FM_LOAD_TILE
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
   __bf16* dkp = (__bf16*)a.dk + (size_t)bh * N * D;
@@ -476,10 +554,10 @@ hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream) {
   const unsigned blocks = (unsigned)((threads + 255) / 256);
   if (a.d == 128)
     hipLaunchKernelGGL(dvec_kernel<128>, dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                       (const __bf16*)a.dout, a.dvec, rows);
+                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, rows);
   else
     hipLaunchKernelGGL(dvec_kernel<64>, dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                       (const __bf16*)a.dout, a.dvec, rows);
+                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, rows);
   return hipGetLastError();
 }
 

@@ -80,6 +80,69 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 
 __device__ __forceinline__ u32x4 ldg16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 
+// LDS layout of a [rows][D] bf16 tile, shared by all tile loops.
+//
+// LDS serves 64 banks x 4 B per clock; a 128-bit read is issued 16 lanes per
+// clock and the 64-bit transpose read 32 lanes per clock.  A tile is read in
+// two ways: as MFMA operand rows (16 consecutive rows, one 16-byte chunk each
+// per clock) and through the transpose read (4 consecutive rows x 64 bytes per
+// clock).  Rows are stored unpadded (the direct global->LDS copy writes 1 KB
+// contiguously per wave) and the 16-byte chunk index of a row is XORed with a
+// bit permutation of the row's low four bits, chosen so that 16 consecutive
+// rows hit 16 different 16-byte slots of the 256-byte bank line (first
+// pattern) and 4 consecutive rows hit 4 different 64-byte groups (second
+// pattern): both reads are conflict-free.
+// off(row + 16*m, col) == off(row, col) + 16*m*RS, so callers precompute the
+// lane-dependent part once.
+template <int D>
+struct TileLayout {
+  static constexpr int RS = D * 2;       // bytes per row
+  static constexpr int CPR = D / 8;      // 16-byte chunks per row
+  static __device__ __forceinline__ int swz(int row) {
+    const int r = row & 15;
+    if (D == 128) return ((r & 3) << 2) | (r >> 2);   // 16 chunks per row, one row per bank line
+    const int a = r >> 1;                               // D == 64: two rows per bank line
+    return ((a & 1) << 2) | (a >> 1);
+  }
+  static __device__ __forceinline__ int off(int row, int byte_col) {
+    return row * RS + ((((byte_col >> 4) ^ swz(row)) << 4) | (byte_col & 15));
+  }
+  // off(row, col0 + colc) from off(row, col0), for a constant colc that is a
+  // multiple of 16 and shares no set bit with col0.
+  static __device__ __forceinline__ int add_col(int base, int colc) { return base ^ colc; }
+};
+
+// Asynchronous global->LDS copy of a [ROWS][D] bf16 tile (global row stride D)
+// into TileLayout<D> order by a 256-thread workgroup.  Every wave instruction
+// moves 64 x 16 B = 1 KB straight into LDS (no staging registers); the
+// swizzle is applied on the global-address side.  `lane_src` is this thread's
+// element offset from async_src_offset(); completion is awaited by the
+// vmcnt(0) that precedes the next workgroup barrier.
+template <int D>
+__device__ __forceinline__ int async_src_offset(int wave, int lane) {
+  using L = TileLayout<D>;
+  constexpr int RPI = 64 / L::CPR;                    // rows per wave instruction
+  const int row = wave * RPI + lane / L::CPR;         // row within the first 4 KB; swizzle repeats every 16 rows
+  return row * D + (((lane % L::CPR) ^ L::swz(row)) << 3);
+}
+template <int D, int ROWS>
+__device__ __forceinline__ void tile_load_async(const __bf16* tile_src, int lane_src, char* lds_tile, int wave) {
+  using L = TileLayout<D>;
+  constexpr int RPI = 64 / L::CPR;
+  constexpr int NINST = ROWS / RPI / 4;
+#pragma unroll
+  for (int s = 0; s < NINST; ++s)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile_src + s * 4 * RPI * D + lane_src),
+                                     (FM_LDS void*)(lds_tile + (s * 4 + wave) * 1024), 16, 0, 0);
+}
+
+// Make a loop-invariant value opaque so that expressions derived from it are
+// recomputed (one VALU op) instead of being kept live in registers.
+__device__ __forceinline__ int opaque(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 // Ordered compaction shared by the tile loops: every thread of a 256-thread
 // workgroup offers one candidate per pass (live or not, with its list entry);
 // live entries are appended to list[] in candidate order.  `running` carries

@@ -18,10 +18,9 @@ template <int D, int QB>
 struct FwdCfg {
   static constexpr int KT = FM_FWD_BC;          // keys per tile
   static constexpr int BR = 128 * QB;           // query rows per workgroup
-  static constexpr int RSK = D * 2 + 16;        // K row stride in LDS (bytes)
-  static constexpr int RSV = D * 2 + 32;        // V row stride in LDS (bytes)
-  static constexpr int K_BYTES = KT * RSK;
-  static constexpr int V_BYTES = KT * RSV;
+  using L = TileLayout<D>;                      // swizzled / padded LDS rows
+  static constexpr int K_BYTES = KT * L::RS;
+  static constexpr int V_BYTES = KT * L::RS;
   static constexpr int BND_BYTES = 4 * KT * 4;  // LTS, LTE, UTS, UTE slices of one tile
   static constexpr int STAGE = K_BYTES + V_BYTES + BND_BYTES;
   static constexpr int LIST_CAP = 1024;         // key blocks classified per pass
@@ -29,7 +28,6 @@ struct FwdCfg {
   static constexpr int CNT_OFF = LIST_CAP * 4;
   static constexpr int STAGE_OFF = CNT_OFF + 64;
   static constexpr int LDS_BYTES = STAGE_OFF + 2 * STAGE;
-  static constexpr int NCH = KT * D / 8 / 256;  // 16-byte chunks per thread per matrix
 };
 
 template <int D, int QB>
@@ -53,8 +51,18 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
   const __bf16* kp = (const __bf16*)a.k + (size_t)bh * N * D;
   const __bf16* vp = (const __bf16*)a.v + (size_t)bh * N * D;
   const int* table = a.minmax + (size_t)b * 8 * t_c;
-  const int *bvec0 = a.lts + (size_t)b * N, *bvec1 = a.lte + (size_t)b * N, *bvec2 = a.uts + (size_t)b * N,
-            *bvec3 = a.ute + (size_t)b * N;
+  // lanes of wave 0 copy the four bound slices of a partially masked tile: lane l moves
+  // 16 bytes of vector l / 16
+  const int* my_bvec;
+  {
+    const int which = lane >> 4;
+    const int* p = a.lts;
+    if (which == 1) p = a.lte;
+    if (which == 2) p = a.uts;
+    if (which == 3) p = a.ute;
+    my_bvec = p + (size_t)b * N + (lane & 15) * 4;
+  }
+  const int lane_src = async_src_offset<D>(wave, lane);
 
   // Q fragments (B operand of S^T = K Q^T): lane holds Q[row c][16 kk + 8 g ..+7].
   bf16x8 qreg[QB][NKK];
@@ -78,41 +86,36 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
 
   int* list = (int*)(smem + C::LIST_OFF);
   int* wave_cnt = (int*)(smem + C::CNT_OFF);
-  const float sc = a.scale * kLog2e;
+  const float sc = a.scale * kLog2e;  // > 0 (checked on the host)
+  // Scores stay raw; exp2(s*sc - m) is one fma + one exp.  The reference
+  // maximum m only moves when a tile's maximum exceeds it by more than
+  // kRescaleGap (log2 units), so the rescale of O and l is rare; any m is a
+  // valid softmax reference, P just grows up to 2^kRescaleGap.
+  constexpr float kRescaleGap = 8.f;
 
-  // Register staging of the next tile: global loads are issued before the
-  // current tile's math and written to the other LDS buffer after it.
-  u32x4 kst[C::NCH], vst[C::NCH], bst[4];
-#define FM_ISSUE_LOADS(ENTRY)                                               \
-  {                                                                         \
-    const int j_ = (ENTRY) & 0xFFFFFF;                                      \
-    _Pragma("unroll") for (int s = 0; s < C::NCH; ++s) {                    \
-      const int ch = tid + 256 * s;                                         \
-      const int row = ch / (D / 8), col = ch % (D / 8);                     \
-      const size_t off = (size_t)(j_ * KT + row) * D + col * 8;             \
-      kst[s] = ldg16(kp + off);                                             \
-      vst[s] = ldg16(vp + off);                                             \
-    }                                                                       \
-    if ((((ENTRY) >> 24) & T_PARTIAL) && tid < KT / 4) {                    \
-      bst[0] = ldg16(bvec0 + j_ * KT + tid * 4);                            \
-      bst[1] = ldg16(bvec1 + j_ * KT + tid * 4);                            \
-      bst[2] = ldg16(bvec2 + j_ * KT + tid * 4);                            \
-      bst[3] = ldg16(bvec3 + j_ * KT + tid * 4);                            \
-    }                                                                       \
-  }
-#define FM_STORE_STAGE(ENTRY, BUF)                                          \
-  {                                                                         \
-    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                     \
-    _Pragma("unroll") for (int s = 0; s < C::NCH; ++s) {                    \
-      const int ch = tid + 256 * s;                                         \
-      const int row = ch / (D / 8), col = ch % (D / 8);                     \
-      *(u32x4*)(st_ + row * C::RSK + col * 16) = kst[s];                    \
-      *(u32x4*)(st_ + C::K_BYTES + row * C::RSV + col * 16) = vst[s];       \
-    }                                                                       \
-    if ((((ENTRY) >> 24) & T_PARTIAL) && tid < KT / 4) {                    \
-      _Pragma("unroll") for (int v_ = 0; v_ < 4; ++v_)                      \
-          *(u32x4*)(st_ + C::K_BYTES + C::V_BYTES + v_ * KT * 4 + tid * 16) = bst[v_]; \
-    }                                                                       \
+  // lane-dependent LDS offsets inside a tile (row block 0)
+  const int i16 = lane & 15, half = (lane >> 4) & 1;
+  int a_off[NKK];       // operand rows: row c, bytes (16 kk + 8 g) * 2
+  int t_off[2][NDB];    // transpose reads: row 4 g + i16/4 (+8), bytes (32 db + 16 half + 4 (i16 & 3)) * 2
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) a_off[kk] = C::L::off(c, (kk * 16 + 8 * g) * 2);
+#pragma unroll
+  for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+      t_off[hi][db] = C::L::off(4 * g + (i16 >> 2) + 8 * hi, (db * 32 + 16 * half + 4 * (i16 & 3)) * 2);
+
+  // Asynchronous copy of one live tile (K, V and, if partially masked, its bound slices)
+  // into stage buffer BUF; awaited by the vmcnt(0) in front of the next barrier.
+#define FM_LOAD_TILE(ENTRY, BUF)                                                               \
+  {                                                                                            \
+    const int j_ = (ENTRY) & 0xFFFFFF;                                                         \
+    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
+    tile_load_async<D, KT>(kp + (size_t)j_ * KT * D, lane_src, st_, wave);                     \
+    tile_load_async<D, KT>(vp + (size_t)j_ * KT * D, lane_src, st_ + C::K_BYTES, wave);        \
+    if ((((ENTRY) >> 24) & T_PARTIAL) && wave == 0)                                            \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(my_bvec + j_ * KT), \
+                                       (FM_LDS void*)(st_ + C::K_BYTES + C::V_BYTES), 16, 0, 0); \
   }
 
   for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
@@ -120,15 +123,14 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
                                              list, wave_cnt);
     if (n_live == 0) continue;
     const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
-    FM_ISSUE_LOADS(first_entry);
-    FM_STORE_STAGE(first_entry, 0);
+    FM_LOAD_TILE(first_entry, 0);
     __syncthreads();
 
     for (int t = 0; t < n_live; ++t) {
       const int entry = __builtin_amdgcn_readfirstlane(list[t]);
       const int j = entry & 0xFFFFFF;
       const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
-      if (t + 1 < n_live) FM_ISSUE_LOADS(next_entry);
+      if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
 
       const char* st = smem + C::STAGE_OFF + (t & 1) * C::STAGE;
       const char* ks = st;
@@ -149,19 +151,11 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
         for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
           for (int kk = 0; kk < NKK; ++kk) {
-            const bf16x8 ka = *(const bf16x8*)(ks + (kb * 32 + c) * C::RSK + (kk * 16 + 8 * g) * 2);
+            const bf16x8 ka = *(const bf16x8*)(ks + kb * 32 * C::L::RS + a_off[kk]);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(ka, qreg[qb][kk], sacc[kb][qb]);
           }
         __builtin_amdgcn_sched_barrier(0);
-        // scaled scores in the log2 domain
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb][qb][r] *= sc;
-
         if (wcls & T_PARTIAL) {
           // Both pairs are applied whenever the tile is partial: a pair whose
           // NEED bit is clear masks no element of this tile, so this is exact,
@@ -196,30 +190,33 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
           for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-          mx = fmaxf(mx, partner32(mx));
-          const float m_new = fmaxf(m_run[qb], mx);
-          const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-          const float alpha = fast_exp2(m_run[qb] - m_use);
-          m_run[qb] = m_new;
+          mx = fmaxf(mx, partner32(mx)) * sc;
+          const bool grow = mx > m_run[qb] + kRescaleGap;   // also true on the first finite maximum
+          if (__any(grow)) {
+            const float m_new = grow ? mx : m_run[qb];
+            const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run[qb] - m_new);
+            m_run[qb] = m_new;
+            l_run[qb] *= alpha;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+          }
+          const float neg_m = (m_run[qb] == -INFINITY) ? 0.f : -m_run[qb];
           float rs = 0.f;
 #pragma unroll
           for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const float p = fast_exp2(sacc[kb][qb][r] - m_use);
+              const float p = fast_exp2(__builtin_fmaf(sacc[kb][qb][r], sc, neg_m));
               sacc[kb][qb][r] = p;
               rs += p;
             }
-          l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+          l_run[qb] += rs;
         }
 
         __builtin_amdgcn_sched_barrier(0);
         // O^T += V^T P^T
-        const int i16 = lane & 15, half = (lane >> 4) & 1;
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
@@ -230,12 +227,11 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
 #pragma unroll
               for (int e = 0; e < 8; ++e) pb[qb][e] = (__bf16)sacc[kb][qb][8 * h + e];
             __builtin_amdgcn_sched_barrier(0);
-            const int row0 = kb * 32 + 16 * h + 4 * g + (i16 >> 2);
+            const char* vrow = vs + (kb * 32 + 16 * h) * C::L::RS;
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-              const int col = db * 32 + 16 * half + 4 * (i16 & 3);
-              const bf16x4 lo = lds_read_tr16(vs + row0 * C::RSV + col * 2);
-              const bf16x4 hi = lds_read_tr16(vs + (row0 + 8) * C::RSV + col * 2);
+              const bf16x4 lo = lds_read_tr16(vrow + t_off[0][db]);
+              const bf16x4 hi = lds_read_tr16(vrow + t_off[1][db]);
               const bf16x8 va = cat4(lo, hi);
 #pragma unroll
               for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(va, pb[qb], oacc[db][qb]);
@@ -243,7 +239,6 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
           }
       }
 
-      if (t + 1 < n_live) FM_STORE_STAGE(next_entry, (t + 1) & 1);
       __syncthreads();
     }
   }
@@ -269,8 +264,7 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
   }
 }
 
-#undef FM_ISSUE_LOADS
-#undef FM_STORE_STAGE
+#undef FM_LOAD_TILE
 
 }  // namespace fm
 

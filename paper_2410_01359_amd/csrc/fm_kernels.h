@@ -47,6 +47,7 @@ struct FmBwdArgs {
   const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
   const int* order_dkdv;
   float* dvec;             // D = rowsum(dO o O), [B,H,N]
+  float* lse2;             // lse * log2(e), +inf where lse = -inf, [B,H,N]
   void *dq, *dk, *dv;
   float scale;
   int B, H, N, d;
