@@ -297,21 +297,27 @@ __device__ __forceinline__ void barrier_nofence() {
 
 // exp / dS arithmetic of elements [e0, e0 + cnt) of one 32x32 block held in the
 // MFMA output layout: register r is query row 8*(r/4) + 4*g + r%4 of the block.
+// The exp / dS arithmetic of one score element, cut into three stages that the
+// tile loop issues in three consecutive steps, so that a step never holds two
+// dependent vector instructions of the same element (one wave per SIMD: nothing
+// else hides the latency of v_exp_f32 and of the AGPR reads):
+//   A: t = s*sc - lse2 (with the element mask), u = dP - D     B: p = exp2(t)     C: dS = p * u
+// Register r of a block is query row 8*(r/4) + 4*g + r%4.
 template <bool MASKED>
-__device__ __forceinline__ void dkdv_elems(f32x16& s, f32x16& dp, const f32x4 (&l4)[4], const f32x4 (&d4)[4], int e0,
-                                           int cnt, int row_base /* r0 + 32*qb + 4*g */, float sc, int b_lts,
-                                           int b_lte, int b_uts, int b_ute) {
+__device__ __forceinline__ void dkdv_stage_a(const f32x16& s, const f32x16& dp, float (&t)[16],
+                                             float (&u)[16], const f32x4 (&l4)[4], const f32x4 (&d4)[4], int e0,
+                                             int cnt, int row_base /* r0 + 32*qb + 4*g */, float sc, int b_lts,
+                                             int b_lte, int b_uts, int b_ute) {
 #pragma unroll
   for (int r = e0; r < e0 + cnt; ++r) {
     float x = s[r];
     if (MASKED) {
       const int qrow = row_base + 8 * (r >> 2) + (r & 3);
-      const bool masked = ((qrow >= b_lts) & (qrow < b_lte)) | ((qrow >= b_uts) & (qrow < b_ute));
-      if (masked) x = -INFINITY;
+      const bool hit = ((qrow >= b_lts) & (qrow < b_lte)) | ((qrow >= b_uts) & (qrow < b_ute));
+      if (hit) x = -INFINITY;
     }
-    const float p = fast_exp2(__builtin_fmaf(x, sc, -l4[r >> 2][r & 3]));
-    s[r] = p;
-    dp[r] = p * (dp[r] - d4[r >> 2][r & 3]);
+    t[r] = __builtin_fmaf(x, sc, -l4[r >> 2][r & 3]);
+    u[r] = dp[r] - d4[r >> 2][r & 3];
   }
 }
 
@@ -333,14 +339,14 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const
   constexpr int NST = 2 * NKK;     // MFMAs per block and product pair
   constexpr int EPS = 16 / NST;    // elements handled next to one MFMA (D = 128: 1, D = 64: 2)
   constexpr int NX = 4 * NST;      // MFMAs per tile
-  constexpr int RD = 4;            // operand fetch distance (steps)
+  constexpr int RD = 6;            // operand fetch distance (steps)
   const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
   // LDS operand of step x
   auto operand = [&](int x) __attribute__((always_inline)) {
     if (x < 2 * NST) {             // row reads: Q or dO rows of block x / NST as MFMA A operand
-      const int qb = x / NST, kk = x % NKK;
-      const char* tile = ((x / NKK) & 1) ? dos : qs;
+      const int qb = x / NST, kk = (x % NST) / 2;
+      const char* tile = (x & 1) ? dos : qs;
       return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, kk * 32));
     }
     // transpose reads: dO (even step, dV) or Q (odd step, dK) as MFMA B operand
@@ -354,6 +360,7 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const
   f32x16 sb[2], pb[2];             // S then P, dP then dS, of the two blocks
   bf16x8 pa[2][2], dsa[2][2];      // bf16 P^T and dS^T, [block][16-row half]
   f32x4 l4[2][4], d4[2][4];        // lse (log2 domain) and D of the blocks' rows, fetched one group of 4 rows ahead
+  float tq[2][16], uq[2][16];      // per element: exponent then P, and dP - D then dS
   auto vec_group = [&](int qb, int grp) __attribute__((always_inline)) {
     l4[qb][grp] = *(const f32x4*)(lse_s + qb * 32 + 8 * grp + 4 * g);
     d4[qb][grp] = *(const f32x4*)(dv_s + qb * 32 + 8 * grp + 4 * g);
@@ -366,8 +373,8 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const
   for (int x = 0; x < NX; ++x) {
     // --- the MFMA of this step
     if (x < 2 * NST) {
-      const int qb = x / NST, kk = x % NKK;
-      if (((x / NKK) & 1) == 0)
+      const int qb = x / NST, kk = (x % NST) / 2;   // S and dP alternate: two independent accumulation chains
+      if ((x & 1) == 0)
         sb[qb] = mfma32(op[x % RD], kreg[kk], kk == 0 ? zero : sb[qb]);
       else
         pb[qb] = mfma32(op[x % RD], vreg[kk], kk == 0 ? zero : pb[qb]);
@@ -380,21 +387,34 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const
     }
     // --- fetch the operand of step x + RD
     if (x + RD < NX) op[x % RD] = operand(x + RD);
-    // --- vector work riding along: block 0 during steps [NST, 2 NST), block 1 during [2 NST, 3 NST)
+    // --- vector work riding along.  Vector step j = x - NST - stage handles EPS elements of
+    //     block j / NST: stage A at x, stage B one step later, stage C two steps later.
     if (x == NST - 1) vec_group(0, 0);
-    if (x == 2 * NST - 1) vec_group(1, 0);
-    if (x >= NST && x < 3 * NST) {
-      const int qb = (x - NST) / NST, e0 = ((x - NST) % NST) * EPS;
-      if (e0 % 4 == 0 && e0 / 4 + 1 < 4) vec_group(qb, e0 / 4 + 1);
-      dkdv_elems<MASKED>(sb[qb], pb[qb], l4[qb], d4[qb], e0, EPS, r0 + 32 * qb + 4 * g, sc, b_lts, b_lte, b_uts, b_ute);
-      if (e0 + EPS == 16) {
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh)
+    for (int stage = 2; stage >= 0; --stage) {
+      const int j = x - NST - stage;
+      if (j >= 0 && j < 2 * NST) {
+        const int qb = j / NST, e0 = (j % NST) * EPS;
+        if (stage == 0) {
+          if (e0 % 4 == 0 && e0 / 4 + 1 < 4) vec_group(qb, e0 / 4 + 1);
+          if (qb == 0 && e0 + EPS == 16) vec_group(1, 0);
+          dkdv_stage_a<MASKED>(sb[qb], pb[qb], tq[qb], uq[qb], l4[qb], d4[qb], e0, EPS, r0 + 32 * qb + 4 * g, sc,
+                       b_lts, b_lte, b_uts, b_ute);
+        } else if (stage == 1) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            pa[qb][hh][e] = (__bf16)sb[qb][8 * hh + e];
-            dsa[qb][hh][e] = (__bf16)pb[qb][8 * hh + e];
+          for (int r = e0; r < e0 + EPS; ++r) tq[qb][r] = fast_exp2(tq[qb][r]);
+        } else {
+#pragma unroll
+          for (int r = e0; r < e0 + EPS; ++r) uq[qb][r] *= tq[qb][r];
+          if ((e0 + EPS) % 8 == 0) {   // a 16-row half of P^T and dS^T is complete: convert it to bf16 operands
+            const int hh = (e0 + EPS) / 8 - 1;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              pa[qb][hh][e] = (__bf16)tq[qb][8 * hh + e];
+              dsa[qb][hh][e] = (__bf16)uq[qb][8 * hh + e];
+            }
           }
+        }
       }
     }
     FM_FENCE();
@@ -488,8 +508,32 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
                                        (FM_LDS void*)(st_ + C::Q_BYTES + C::DO_BYTES), 16, 0, 0); \
   }
 
+  // One pass of the tile loop over list entries [T0, T1) with the element mask compiled in or
+  // out.  Tiles that need no element mask are listed first and run through the mask-free
+  // instantiation, partially masked ones (for the workgroup's 128 keys) through the other;
+  // keeping the two instantiations in separate loops keeps the 128 accumulator registers where
+  // they are (merged into one loop, the compiler shuffled all of them every tile).
+#define FM_TILE_LOOP(T0, T1, MASKED)                                                                   \
+  for (int t = (T0); t < (T1); ++t) {                                                                  \
+    /* tile t has landed once at most min(NSTAGE - 2, tiles after t) later copies are in flight */     \
+    wait_tile_landed<C::COPIES>(min(C::NSTAGE - 2, n_live - 1 - t), wave == 0);                        \
+    barrier_nofence(); /* every wave's part of tile t is in LDS; every wave is done with tile t-1 */   \
+    if (t + C::NSTAGE - 1 < n_live) {                                                                  \
+      const int e = __builtin_amdgcn_readfirstlane(list[t + C::NSTAGE - 1]);                           \
+      FM_LOAD_TILE(e, (t + C::NSTAGE - 1) % C::NSTAGE);                                                \
+    }                                                                                                  \
+    const int i_blk = __builtin_amdgcn_readfirstlane(list[t]) & 0xFFFFFF;                              \
+    const char* st = smem + C::STAGE_OFF + (t % C::NSTAGE) * C::STAGE;                                 \
+    const float* lse_s = (const float*)(st + C::Q_BYTES + C::DO_BYTES);                                \
+    const int r0 = i_blk * QT;                                                                         \
+    if (classify_tile(r0, min(r0 + QT, N), wmm) != T_FULLY)                                            \
+      dkdv_tile<D, MASKED>(st, st + C::Q_BYTES, lse_s, lse_s + QT, kreg, vreg, dkacc, dvacc, a_base,   \
+                           t_base0, t_base1, r0, g, sc, b_lts, b_lte, b_uts, b_ute);                   \
+  }
+
   for (int chunk = 0; chunk < t_r; chunk += C::LIST_CAP) {
-    const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, t_r), list, wave_cnt);
+    int n_plain = 0;
+    const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, t_r), list, wave_cnt, n_plain);
     if (n_live == 0) continue;
     // prologue: copies of the first NSTAGE - 1 tiles
 #pragma unroll
@@ -498,37 +542,11 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
         const int e = __builtin_amdgcn_readfirstlane(list[p]);
         FM_LOAD_TILE(e, p);
       }
-
-    for (int t = 0; t < n_live; ++t) {
-      // tile t has landed once at most min(NSTAGE - 2, tiles after t) later copies are in flight
-      wait_tile_landed<C::COPIES>(min(C::NSTAGE - 2, n_live - 1 - t), wave == 0);
-      barrier_nofence();   // every wave's part of tile t is in LDS; every wave is done with tile t - 1
-      if (t + C::NSTAGE - 1 < n_live) {
-        const int e = __builtin_amdgcn_readfirstlane(list[t + C::NSTAGE - 1]);
-        FM_LOAD_TILE(e, (t + C::NSTAGE - 1) % C::NSTAGE);
-      }
-      const int entry = __builtin_amdgcn_readfirstlane(list[t]);
-      const int i_blk = entry & 0xFFFFFF;
-
-      const char* st = smem + C::STAGE_OFF + (t % C::NSTAGE) * C::STAGE;
-      const char* qs = st;
-      const char* dos = st + C::Q_BYTES;
-      const float* lse_s = (const float*)(st + C::Q_BYTES + C::DO_BYTES);
-      const float* dv_s = lse_s + QT;
-      const int r0 = i_blk * QT;
-
-      const int wcls = classify_tile(r0, min(r0 + QT, N), wmm);
-      if (wcls != T_FULLY) {
-        if (wcls & T_PARTIAL)
-          dkdv_tile<D, true>(qs, dos, lse_s, dv_s, kreg, vreg, dkacc, dvacc, a_base, t_base0, t_base1, r0, g, sc, b_lts,
-                             b_lte, b_uts, b_ute);
-        else
-          dkdv_tile<D, false>(qs, dos, lse_s, dv_s, kreg, vreg, dkacc, dvacc, a_base, t_base0, t_base1, r0, g, sc,
-                              b_lts, b_lte, b_uts, b_ute);
-      }
-    }
+    FM_TILE_LOOP(0, n_plain, false)
+    FM_TILE_LOOP(n_plain, n_live, true)
     __syncthreads();   // the list and the ring are rebuilt by the next chunk
   }
+#undef FM_TILE_LOOP
 #undef FM_LOAD_TILE
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]

@@ -181,15 +181,22 @@ __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ tab
 }
 
 // Column-parallel loop: classify row blocks [i_begin, i_end) of block_r rows
-// against one key block's min/max values; entries are i | class << 24.
+// against one key block's min/max values; entries are i | class << 24.  The
+// blocks that need no element mask come first (n_plain of them), the partially
+// masked ones after, each group in ascending order.
 __device__ __forceinline__ int build_live_row_blocks(const MinMax8& t, int n, int block_r, int i_begin, int i_end,
-                                                     int* list, int* wave_cnt) {
+                                                     int* list, int* wave_cnt, int& n_plain) {
   int running = 0;
-  for (int base = i_begin; base < i_end; base += 256) {
-    const int i = base + threadIdx.x;
-    int cls = T_FULLY;
-    if (i < i_end) cls = classify_tile(i * block_r, min((i + 1) * block_r, n), t);
-    append_live(cls != T_FULLY, i | (cls << 24), list, wave_cnt, running);
+#pragma unroll 1
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int base = i_begin; base < i_end; base += 256) {
+      const int i = base + threadIdx.x;
+      int cls = T_FULLY;
+      if (i < i_end) cls = classify_tile(i * block_r, min((i + 1) * block_r, n), t);
+      const bool want = (pass == 0) ? (cls == T_UNMASKED) : ((cls & T_PARTIAL) != 0);
+      append_live(want, i | (cls << 24), list, wave_cnt, running);
+    }
+    if (pass == 0) n_plain = running;
   }
   return running;
 }
