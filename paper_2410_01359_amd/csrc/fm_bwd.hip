@@ -126,26 +126,25 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 
 #define FM_LOAD_TILE(ENTRY, BUF)                                                               \
   {                                                                                            \
-    const int j_ = (ENTRY) & 0xFFFFFF;                                                         \
+    const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
     tile_load_async<D, KT>(kp + (size_t)j_ * KT * D, lane_src, st_, wave);                     \
     tile_load_async<D, KT>(vp + (size_t)j_ * KT * D, lane_src, st_ + C::K_BYTES, wave);        \
-    if ((((ENTRY) >> 24) & T_PARTIAL) && wave == 0)                                            \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(my_bvec + j_ * KT), \
-                                       (FM_LDS void*)(st_ + C::K_BYTES + C::V_BYTES), 16, 0, 0); \
+    if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
+      async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
   }
 
   for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N),
-                                             list, wave_cnt);
+                                             C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
     const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
     FM_LOAD_TILE(first_entry, 0);
-    __syncthreads();
+    async_wait<0>();
+    barrier_nofence();
 
     for (int t = 0; t < n_live; ++t) {
       const int entry = __builtin_amdgcn_readfirstlane(list[t]);
-      const int j = entry & 0xFFFFFF;
       const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
       if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
 
@@ -154,7 +153,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
       const char* vs = st + C::K_BYTES;
       const int* bnd = (const int*)(st + C::K_BYTES + C::V_BYTES);
 
-      const int wcls = classify_tile(qw0, qw0 + 32, load_minmax(table, t_c, j));
+      const int wcls = entry_wave_class(entry, wave);   // Equation 4 on this wave's own rows
       if (wcls != T_FULLY) {
         const int a_b = opaque(a_base), t_b0 = opaque(t_base0), t_b1 = opaque(t_base1);
 #pragma unroll
@@ -214,8 +213,10 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
         }
       }
 
-      __syncthreads();
+      async_wait<0>();   // the next tile has landed ...
+      barrier_nofence(); // ... for every wave, and every wave is done reading this one
     }
+    __syncthreads();     // the list is rebuilt by the next pass
   }
 #undef FM_LOAD_TILE
 
@@ -273,24 +274,14 @@ struct DkdvCfg {
 template <int COPIES>
 __device__ __forceinline__ void wait_tile_landed(int tiles_behind, bool extra_copy) {
   if (extra_copy) {
-    if (tiles_behind >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (COPIES + 1)) : "memory");
-    else if (tiles_behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(COPIES + 1) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (tiles_behind >= 2) async_wait<2 * (COPIES + 1)>();
+    else if (tiles_behind == 1) async_wait<COPIES + 1>();
+    else async_wait<0>();
   } else {
-    if (tiles_behind >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * COPIES) : "memory");
-    else if (tiles_behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(COPIES) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (tiles_behind >= 2) async_wait<2 * COPIES>();
+    else if (tiles_behind == 1) async_wait<COPIES>();
+    else async_wait<0>();
   }
-}
-
-// Workgroup barrier without the memory fence of __syncthreads() (which would
-// drain every outstanding async copy): the caller has already waited for the
-// copies that must be visible, and all LDS reads of the tile being replaced
-// were consumed by MFMAs before the wave got here.
-__device__ __forceinline__ void barrier_nofence() {
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
 }
 
 #define FM_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -503,9 +494,7 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                          \
     tile_load_async<D, QT>(qp + (size_t)i_ * QT * D, lane_src, st_, wave);                       \
     tile_load_async<D, QT>(dop + (size_t)i_ * QT * D, lane_src, st_ + C::Q_BYTES, wave);         \
-    if (wave == 0 && lane < 32)                                                                  \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(my_vec + i_ * QT), \
-                                       (FM_LDS void*)(st_ + C::Q_BYTES + C::DO_BYTES), 16, 0, 0); \
+    if (wave == 0 && lane < 32) async_copy16(my_vec + i_ * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES)); \
   }
 
   // One pass of the tile loop over list entries [T0, T1) with the element mask compiled in or

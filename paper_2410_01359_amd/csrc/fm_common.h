@@ -125,15 +125,48 @@ __device__ __forceinline__ int async_src_offset(int wave, int lane) {
   const int row = wave * RPI + lane / L::CPR;         // row within the first 4 KB; swizzle repeats every 16 rows
   return row * D + (((lane % L::CPR) ^ L::swz(row)) << 3);
 }
+// One wave-wide asynchronous copy: every active lane moves 16 bytes from its own
+// global address to LDS address lds_addr + 16 * lane (lds_addr wave-uniform).
+// Issued through inline assembly on purpose: the compiler treats the builtin
+// form as an LDS store that any later LDS read may alias and drains ALL
+// outstanding copies (s_waitcnt vmcnt(0)) in front of the next LDS read, which
+// would serialise the copy of the next tiles with the math of this one.  Here
+// the waiting is explicit: async_wait<N>() before the barrier that publishes a
+// tile.  (Copies complete in issue order; counting extra outstanding vector
+// memory operations only ever makes the compiler's own vmcnt waits stricter.)
+__device__ __forceinline__ void async_copy16(const void* gsrc, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gsrc)
+               : "memory", "m0");
+}
+__device__ __forceinline__ unsigned lds_address(const void* lds_generic) {
+  return (unsigned)(size_t)((FM_LDS const char*)lds_generic);
+}
+// Wait until at most N of this wave's vector-memory operations (async copies
+// included) are still in flight.
+template <int N>
+__device__ __forceinline__ void async_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Workgroup barrier without the memory fence of __syncthreads(): the caller has
+// already waited for the async copies that must be visible, and every LDS read
+// of the buffer about to be overwritten was consumed by an MFMA before the
+// wave got here.
+__device__ __forceinline__ void barrier_nofence() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 template <int D, int ROWS>
 __device__ __forceinline__ void tile_load_async(const __bf16* tile_src, int lane_src, char* lds_tile, int wave) {
   using L = TileLayout<D>;
   constexpr int RPI = 64 / L::CPR;
   constexpr int NINST = ROWS / RPI / 4;
+  const unsigned base = lds_address(lds_tile) + wave * 1024;
 #pragma unroll
-  for (int s = 0; s < NINST; ++s)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile_src + s * 4 * RPI * D + lane_src),
-                                     (FM_LDS void*)(lds_tile + (s * 4 + wave) * 1024), 16, 0, 0);
+  for (int s = 0; s < NINST; ++s) async_copy16(tile_src + s * 4 * RPI * D + lane_src, base + s * 4096);
 }
 
 // Make a loop-invariant value opaque so that expressions derived from it are
@@ -165,20 +198,39 @@ __device__ __forceinline__ void append_live(bool live, int entry, int* list, int
   __syncthreads();
 }
 
-// Row-parallel loops: classify key blocks [j_begin, j_end) against rows [r0, r1)
-// (Equation 4) and list the ones that are not fully masked, in order, as
-// j | class << 24.  Returns the count (uniform over the workgroup).
+// Row-parallel loops: classify key blocks [j_begin, j_end) against the
+// workgroup's rows [r0, r1) (Equation 4) and list the ones that are not fully
+// masked, in order.  Each of the four waves owns rows_per_wave consecutive rows
+// of the block and skips what Equation 4 proves fully masked for ITS rows (and
+// skips the element mask where its rows are unmasked), so the entry also
+// carries the class of each wave's sub-block -- computed here, once, from
+// values already in registers, instead of re-reading the table every tile:
+//   bits 0-15  j - j_begin      bits 16-17  class of the workgroup's tile
+//   bits 18-25 class of wave w's sub-tile in bits 18+2w, 19+2w   (0 unmasked, 1 partial, 2 fully)
+// Returns the number of entries (uniform over the workgroup).
 __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ table, int t_c, int j_begin, int j_end,
-                                                     int r0, int r1, int* list, int* wave_cnt) {
+                                                     int r0, int r1, int rows_per_wave, int* list, int* wave_cnt) {
   int running = 0;
   for (int base = j_begin; base < j_end; base += 256) {
     const int j = base + threadIdx.x;
-    int cls = T_FULLY;
-    if (j < j_end) cls = classify_tile(r0, r1, load_minmax(table, t_c, j));
-    append_live(cls != T_FULLY, j | (cls << 24), list, wave_cnt, running);
+    int cls = T_FULLY, entry = 0;
+    if (j < j_end) {
+      const MinMax8 mm = load_minmax(table, t_c, j);
+      cls = classify_tile(r0, r1, mm);
+      entry = (j - j_begin) | ((cls & 3) << 16);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int w0 = min(r0 + w * rows_per_wave, r1), w1 = min(w0 + rows_per_wave, r1);
+        entry |= (classify_tile(w0, w1, mm) & 3) << (18 + 2 * w);
+      }
+    }
+    append_live(cls != T_FULLY, entry, list, wave_cnt, running);
   }
   return running;
 }
+__device__ __forceinline__ int entry_block(int entry, int j_begin) { return j_begin + (entry & 0xFFFF); }
+__device__ __forceinline__ int entry_tile_class(int entry) { return (entry >> 16) & 3; }
+__device__ __forceinline__ int entry_wave_class(int entry, int wave) { return (entry >> (18 + 2 * wave)) & 3; }
 
 // Column-parallel loop: classify row blocks [i_begin, i_end) of block_r rows
 // against one key block's min/max values; entries are i | class << 24.  The

@@ -106,29 +106,28 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
       t_off[hi][db] = C::L::off(4 * g + (i16 >> 2) + 8 * hi, (db * 32 + 16 * half + 4 * (i16 & 3)) * 2);
 
   // Asynchronous copy of one live tile (K, V and, if partially masked, its bound slices)
-  // into stage buffer BUF; awaited by the vmcnt(0) in front of the next barrier.
+  // into stage buffer BUF; awaited by async_wait<0>() in front of the next barrier.
 #define FM_LOAD_TILE(ENTRY, BUF)                                                               \
   {                                                                                            \
-    const int j_ = (ENTRY) & 0xFFFFFF;                                                         \
+    const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
     tile_load_async<D, KT>(kp + (size_t)j_ * KT * D, lane_src, st_, wave);                     \
     tile_load_async<D, KT>(vp + (size_t)j_ * KT * D, lane_src, st_ + C::K_BYTES, wave);        \
-    if ((((ENTRY) >> 24) & T_PARTIAL) && wave == 0)                                            \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(my_bvec + j_ * KT), \
-                                       (FM_LDS void*)(st_ + C::K_BYTES + C::V_BYTES), 16, 0, 0); \
+    if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
+      async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
   }
 
   for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N),
-                                             list, wave_cnt);
+                                             C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
     const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
     FM_LOAD_TILE(first_entry, 0);
-    __syncthreads();
+    async_wait<0>();
+    barrier_nofence();
 
     for (int t = 0; t < n_live; ++t) {
       const int entry = __builtin_amdgcn_readfirstlane(list[t]);
-      const int j = entry & 0xFFFFFF;
       const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
       if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
 
@@ -137,8 +136,7 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
       const char* vs = st + C::K_BYTES;
       const int* bnd = (const int*)(st + C::K_BYTES + C::V_BYTES);
 
-      // this wave's own rows against the same table entry (Equation 4 on a sub-block)
-      const int wcls = classify_tile(qw0, qw0 + 32 * QB, load_minmax(table, t_c, j));
+      const int wcls = entry_wave_class(entry, wave);   // Equation 4 on this wave's own rows
       if (wcls != T_FULLY) {
         f32x16 sacc[NKB][QB];
 #pragma unroll
@@ -239,8 +237,10 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
           }
       }
 
-      __syncthreads();
+      async_wait<0>();   // the next tile has landed ...
+      barrier_nofence(); // ... for every wave, and every wave is done reading this one
     }
+    __syncthreads();     // the list is rebuilt by the next pass
   }
 
   // epilogue: O / l, lse = m + log(l)   (m, l in the log2 domain)
