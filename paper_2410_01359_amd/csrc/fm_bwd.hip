@@ -106,8 +106,15 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     doreg[kk] = *(const bf16x8*)(dop + (size_t)row * D + kk * 16 + 8 * g);
   }
   // lse in the log2 domain (+inf for a row with no visible key, so that P = 0 there)
-  const float lse2 = a.lse2[(size_t)bh * N + row];
-  const float dsum = a.dvec[(size_t)bh * N + row];
+  float lse2 = a.lse2[(size_t)bh * N + row];
+  float dsum = a.dvec[(size_t)bh * N + row];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    settle(qreg[kk]);
+    settle(doreg[kk]);
+  }
+  settle(lse2);
+  settle(dsum);
 
   f32x16 dqacc[NDB];
 #pragma unroll
@@ -446,8 +453,17 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     vreg[kk] = *(const bf16x8*)(vp + (size_t)key * D + kk * 16 + 8 * g);
   }
   // the four bounds of this lane's key stay in registers (Algorithm 2 loads them once per key block)
-  const int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
-  const int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
+  int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
+  int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    settle(kreg[kk]);
+    settle(vreg[kk]);
+  }
+  settle(b_lts);
+  settle(b_lte);
+  settle(b_uts);
+  settle(b_ute);
   // min/max over this wave's 32 keys, for the wave-level tile class
   MinMax8 wmm;
   {

@@ -169,6 +169,17 @@ __device__ __forceinline__ void tile_load_async(const __bf16* tile_src, int lane
   for (int s = 0; s < NINST; ++s) async_copy16(tile_src + s * 4 * RPI * D + lane_src, base + s * 4096);
 }
 
+// Force a value that was fetched with an ordinary global load to be complete
+// (and known complete to the compiler) at this point.  The tile loops issue
+// their async copies behind the compiler's back; if the first use of such a
+// value sat inside a loop, the compiler's own "s_waitcnt vmcnt(n)" there --
+// counted without the async copies -- would drain the copies of the tiles
+// being prefetched on every iteration.
+template <class T>
+__device__ __forceinline__ void settle(T& x) {
+  asm volatile("" : "+v"(x));
+}
+
 // Make a loop-invariant value opaque so that expressions derived from it are
 // recomputed (one VALU op) instead of being kept live in registers.
 __device__ __forceinline__ int opaque(int x) {

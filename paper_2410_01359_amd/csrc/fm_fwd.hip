@@ -71,6 +71,10 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk)
       qreg[qb][kk] = *(const bf16x8*)(qp + (size_t)(qw0 + qb * 32 + c) * D + kk * 16 + 8 * g);
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) settle(qreg[qb][kk]);
 
   f32x16 oacc[NDB][QB];
   float m_run[QB], l_run[QB];
