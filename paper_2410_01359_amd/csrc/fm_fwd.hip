@@ -149,14 +149,35 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
           for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+        // S^T = K Q^T.  The K operand of step n (chain kb = n % NKB, slice kk = n / NKB: the
+        // accumulation chains alternate) is fetched RS steps ahead into a small register ring,
+        // so an MFMA never waits for a read issued just before it.
+        constexpr int NS = NKB * NKK, RS = 6;
+        bf16x8 kring[RS];
+        auto k_operand = [&](int n) __attribute__((always_inline)) {
+          return *(const bf16x8*)(ks + (n % NKB) * 32 * C::L::RS + a_off[n / NKB]);
+        };
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
+        for (int n = 0; n < RS; ++n) kring[n] = k_operand(n);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int kk = 0; kk < NKK; ++kk) {
-            const bf16x8 ka = *(const bf16x8*)(ks + kb * 32 * C::L::RS + a_off[kk]);
+        for (int n = 0; n < NS; ++n) {
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(ka, qreg[qb][kk], sacc[kb][qb]);
-          }
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[n % NKB][qb] = mfma32(kring[n % RS], qreg[qb][n / NKB], sacc[n % NKB][qb]);
+          if (n + RS < NS) kring[n % RS] = k_operand(n + RS);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // The V operands of the second product do not depend on the scores: start fetching them
+        // now, so they arrive while the softmax arithmetic runs.
+        constexpr int NP = NKB * 2 * NDB, RP = 4;
+        bf16x8 vring[RP];
+        auto v_operand = [&](int n) __attribute__((always_inline)) {
+          const char* vrow = vs + ((n / NDB) * 16) * C::L::RS;   // group n / NDB = (kb, h): 16 keys each
+          return cat4(lds_read_tr16(vrow + t_off[0][n % NDB]), lds_read_tr16(vrow + t_off[1][n % NDB]));
+        };
+#pragma unroll
+        for (int n = 0; n < RP; ++n) vring[n] = v_operand(n);
         __builtin_amdgcn_sched_barrier(0);
         if (wcls & T_PARTIAL) {
           // Both pairs are applied whenever the tile is partial: a pair whose
@@ -218,27 +239,20 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
         }
 
         __builtin_amdgcn_sched_barrier(0);
-        // O^T += V^T P^T
+        // O^T += V^T P^T, step n = (16-key group n / NDB, d block n % NDB)
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
+        for (int n = 0; n < NP; ++n) {
+          const int grp = n / NDB, kb = grp / 2, h = grp % 2, db = n % NDB;
+          bf16x8 pb[QB];
 #pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            bf16x8 pb[QB];
+          for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
+            for (int e = 0; e < 8; ++e) pb[qb][e] = (__bf16)sacc[kb][qb][8 * h + e];
 #pragma unroll
-              for (int e = 0; e < 8; ++e) pb[qb][e] = (__bf16)sacc[kb][qb][8 * h + e];
-            __builtin_amdgcn_sched_barrier(0);
-            const char* vrow = vs + (kb * 32 + 16 * h) * C::L::RS;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-              const bf16x4 lo = lds_read_tr16(vrow + t_off[0][db]);
-              const bf16x4 hi = lds_read_tr16(vrow + t_off[1][db]);
-              const bf16x8 va = cat4(lo, hi);
-#pragma unroll
-              for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(va, pb[qb], oacc[db][qb]);
-            }
-          }
+          for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(vring[n % RP], pb[qb], oacc[db][qb]);
+          if (n + RP < NP) vring[n % RP] = v_operand(n + RP);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
 
       async_wait<0>();   // the next tile has landed ...
