@@ -158,6 +158,9 @@ def main():
     ap.add_argument("--others", default="2,3,4a,4b", help="extra workloads reported in `other_workloads` ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run plain device copies of this many MiB (read once, written once): a kernel of known "
+                         "HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (batch x heads is the sharding axis; see DESIGN.md); "
@@ -184,6 +187,15 @@ def main():
         others.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
                        if k in ("workload", "ms_per_step", "tflops", "block_sparsity", "fwd_ms", "bwd_ms")})
         torch.cuda.empty_cache()
+
+    if args.copy_calibration_mib > 0:
+        n = args.copy_calibration_mib * (1 << 20) // 4
+        src = torch.arange(n, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     st = main_res["stage_ms"]
     dominant = max(("fwd_tiles", "bwd_dkdv", "bwd_dq"), key=lambda k: st[k])

@@ -271,24 +271,19 @@ struct DkdvCfg {
   // trip to L2/HBM, so tiles are copied three steps ahead into a ring of four.
   static constexpr int NSTAGE = 4;
   static constexpr int LDS_BYTES = STAGE_OFF + NSTAGE * STAGE;
-  // async copy instructions one wave issues per tile (wave 0 issues one more, for lse / D)
+  // async copy instructions one wave issues per tile: COPIES for its quarter of Q and dO plus
+  // one for its quarter of the lse / D slice.  Every wave issues the same number for every
+  // tile, so "tile landed" is a constant outstanding-copy count.
   static constexpr int COPIES = 2 * (QT / (64 / L::CPR) / 4);
+  static constexpr int NC = COPIES + 1;
+  // MFMA operand fetch distance in steps; divides the steps per tile, so ring slots line up across tiles
+  static constexpr int RD = 8;
 };
 
-// Wait until at most `tiles_behind` later tile copies of this wave are still in
-// flight (the copies complete in issue order), i.e. until the tile issued
-// before them has landed in LDS.
-template <int COPIES>
-__device__ __forceinline__ void wait_tile_landed(int tiles_behind, bool extra_copy) {
-  if (extra_copy) {
-    if (tiles_behind >= 2) async_wait<2 * (COPIES + 1)>();
-    else if (tiles_behind == 1) async_wait<COPIES + 1>();
-    else async_wait<0>();
-  } else {
-    if (tiles_behind >= 2) async_wait<2 * COPIES>();
-    else if (tiles_behind == 1) async_wait<COPIES>();
-    else async_wait<0>();
-  }
+// lse / D slice of a tile in LDS: wave w copies rows 16w..16w+15 as 128 contiguous bytes,
+// 64 bytes of lse then 64 bytes of D.  Float offset of row r (r % 4 == 0 for the 16-byte reads):
+__device__ __forceinline__ constexpr int dkdv_vec_off(int r, bool d_part) {
+  return (r >> 4) * 32 + (d_part ? 16 : 0) + (r & 15);
 }
 
 #define FM_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -319,54 +314,104 @@ __device__ __forceinline__ void dkdv_stage_a(const f32x16& s, const f32x16& dp, 
   }
 }
 
+// What the tail of a tile's stream does for the tiles that follow it.
+struct DkdvAhead {
+  const char* nqs;        // LDS: stage of the next list entry (its Q tile; dO follows), for the operand prefetch
+  int v_copy;             // list entry (still in a vector register) of the tile NSTAGE - 1 ahead, to be copied
+  const char* q_base;     // global Q / dO of this (batch, head) and this lane's lse2 / D source
+  const char* do_base;
+  const float* vec_src;
+  unsigned lds_ring;      // LDS address of stage 0
+  unsigned stage_copy;    // index of the stage that receives the copy
+  unsigned lane_off;      // this lane's byte offset inside a 4 KB copy group
+  int wave;
+};
+
+// Copy number K (of NC) of the tile whose 64-row base offsets are given.
+template <int D, int K>
+__device__ __forceinline__ void dkdv_issue_copy(const DkdvAhead& ah, const char* q_src, const char* do_src,
+                                                const float* vec_src, unsigned lds_stage) {
+  using C = DkdvCfg<D>;
+  constexpr int HALF = C::COPIES / 2;
+  if (K < HALF)
+    async_copy16_sbase(q_src + K * 4096, ah.lane_off, lds_stage + ah.wave * 1024 + K * 4096);
+  else if (K < C::COPIES)
+    async_copy16_sbase(do_src + (K - HALF) * 4096, ah.lane_off,
+                       lds_stage + C::Q_BYTES + ah.wave * 1024 + (K - HALF) * 4096);
+  else
+    async_copy16_lanes8(vec_src, lds_stage + C::Q_BYTES + C::DO_BYTES + ah.wave * 128);
+}
+
+// LDS operand of step x of the tile whose Q tile starts at qs (dO tile right behind it)
+template <int D>
+__device__ __forceinline__ bf16x8 dkdv_operand(const char* qs, int x, int a_base, int t_base0, int t_base1) {
+  using L = TileLayout<D>;
+  constexpr int NKK = D / 16, NDB = D / 32, NST = 2 * NKK;
+  const char* dos = qs + DkdvCfg<D>::Q_BYTES;
+  if (x < 2 * NST) {             // row reads: Q or dO rows of block x / NST as MFMA A operand
+    const int qb = x / NST, kk = (x % NST) / 2;
+    const char* tile = (x & 1) ? dos : qs;
+    return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, kk * 32));
+  }
+  // transpose reads: dO (even step, dV) or Q (odd step, dK) as MFMA B operand
+  const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
+  const char* tile = (u & 1) ? qs : dos;
+  const char* rowp = tile + (qb * 32 + 16 * h) * L::RS;
+  return cat4(lds_read_tr16(rowp + L::add_col(t_base0, db * 64)), lds_read_tr16(rowp + L::add_col(t_base1, db * 64)));
+}
+
+// The workgroup-level step that every wave takes once per list entry, in the middle of the
+// entry's stream : wait for this wave's part of the
+// NEXT entry's tile, meet the other waves (so the next tile is complete in LDS and nobody
+// still reads the previous one), then the caller refills the previous tile's stage.
+template <int D>
+__device__ __forceinline__ void dkdv_sync() {
+  async_wait<DkdvCfg<D>::NC>();   // copies complete in order: only the tile after the next may be in flight
+  barrier_nofence();
+}
+
 // One 64-row tile = two 32-row blocks.  The tile's 8*NKK MFMAs form one stream
 //   [S0 | dP0 | S1 | dP1 | dV,dK of block 0 | dV,dK of block 1]      (NKK = D/16 MFMAs per bar, 2*NKK for dV,dK)
 // each taking one operand from LDS (a 128-bit row read for the first four
 // groups, a transpose read for the rest) that is fetched RD steps ahead into a
 // small register ring.  The exp / dS arithmetic of block 0 is spread over the
 // steps of S1 and dP1, that of block 1 over the dV,dK steps of block 0, so the
-// vector work always has matrix work in flight beside it.
+// vector work always has matrix work in flight beside it.  The stream runs on
+// into the next list entry: near its end the wave takes the workgroup step
+// (dkdv_sync), issues the copies of the tile NSTAGE - 1 entries ahead one per
+// step, and its last RD operand fetches already read the next entry's tile, so
+// the MFMA pipe does not drain between tiles.  On entry `op` holds the operands
+// of steps 0..RD-1 of this tile, on exit those of the next one.
 template <int D, bool MASKED>
-__device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const float* lse_s, const float* dv_s,
-                                          const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
-                                          f32x16 (&dkacc)[D / 32], f32x16 (&dvacc)[D / 32], int a_base, int t_base0,
-                                          int t_base1, int r0, int g, float sc, int b_lts, int b_lte, int b_uts,
-                                          int b_ute) {
-  using L = TileLayout<D>;
+__device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, const DkdvAhead& ah,
+                                          bf16x8 (&op)[DkdvCfg<D>::RD], const bf16x8 (&kreg)[D / 16],
+                                          const bf16x8 (&vreg)[D / 16], f32x16 (&dkacc)[D / 32],
+                                          f32x16 (&dvacc)[D / 32], int a_base, int t_base0, int t_base1, int r0,
+                                          int g, float sc, int b_lts, int b_lte, int b_uts, int b_ute) {
+  using C = DkdvCfg<D>;
   constexpr int NKK = D / 16, NDB = D / 32;
   constexpr int NST = 2 * NKK;     // MFMAs per block and product pair
   constexpr int EPS = 16 / NST;    // elements handled next to one MFMA (D = 128: 1, D = 64: 2)
   constexpr int NX = 4 * NST;      // MFMAs per tile
-  constexpr int RD = 6;            // operand fetch distance (steps)
+  constexpr int RD = C::RD;
+  constexpr int XS = NX - (C::NC > RD ? C::NC : RD);   // step of the workgroup sync; the copies follow one per step
+  static_assert(NX % RD == 0 && XS > 0, "ring layout");
   const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-  // LDS operand of step x
-  auto operand = [&](int x) __attribute__((always_inline)) {
-    if (x < 2 * NST) {             // row reads: Q or dO rows of block x / NST as MFMA A operand
-      const int qb = x / NST, kk = (x % NST) / 2;
-      const char* tile = (x & 1) ? dos : qs;
-      return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, kk * 32));
-    }
-    // transpose reads: dO (even step, dV) or Q (odd step, dK) as MFMA B operand
-    const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
-    const char* tile = (u & 1) ? qs : dos;
-    const char* rowp = tile + (qb * 32 + 16 * h) * L::RS;
-    return cat4(lds_read_tr16(rowp + L::add_col(t_base0, db * 64)), lds_read_tr16(rowp + L::add_col(t_base1, db * 64)));
-  };
-
-  bf16x8 op[RD];
   f32x16 sb[2], pb[2];             // S then P, dP then dS, of the two blocks
   bf16x8 pa[2][2], dsa[2][2];      // bf16 P^T and dS^T, [block][16-row half]
   f32x4 l4[2][4], d4[2][4];        // lse (log2 domain) and D of the blocks' rows, fetched one group of 4 rows ahead
   float tq[2][16], uq[2][16];      // per element: exponent then P, and dP - D then dS
   auto vec_group = [&](int qb, int grp) __attribute__((always_inline)) {
-    l4[qb][grp] = *(const f32x4*)(lse_s + qb * 32 + 8 * grp + 4 * g);
-    d4[qb][grp] = *(const f32x4*)(dv_s + qb * 32 + 8 * grp + 4 * g);
+    const int row = qb * 32 + 8 * grp + 4 * g;
+    l4[qb][grp] = *(const f32x4*)(vec_s + dkdv_vec_off(row, false));
+    d4[qb][grp] = *(const f32x4*)(vec_s + dkdv_vec_off(row, true));
   };
+  const char* q_src = nullptr;
+  const char* do_src = nullptr;
+  const float* vec_src = nullptr;
+  unsigned lds_stage = 0;
 
-#pragma unroll
-  for (int x = 0; x < RD; ++x) op[x] = operand(x);
-  FM_FENCE();
 #pragma unroll
   for (int x = 0; x < NX; ++x) {
     // --- the MFMA of this step
@@ -383,8 +428,33 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const char* dos, const
       else
         dvacc[db] = mfma32(pa[qb][h], op[x % RD], dvacc[db]);
     }
-    // --- fetch the operand of step x + RD
-    if (x + RD < NX) op[x % RD] = operand(x + RD);
+    // --- the workgroup step and the copies behind it
+    if (x == XS) {
+      dkdv_sync<D>();
+      const int i_copy = __builtin_amdgcn_readfirstlane(ah.v_copy) & 0xFFFFFF;
+      q_src = ah.q_base + (size_t)i_copy * (C::QT * D * 2);
+      do_src = ah.do_base + (size_t)i_copy * (C::QT * D * 2);
+      vec_src = ah.vec_src + i_copy * C::QT;
+      lds_stage = ah.lds_ring + ah.stage_copy * C::STAGE;
+    }
+    if (x >= XS && x < XS + C::NC) {
+      switch (x - XS) {
+        case 0: dkdv_issue_copy<D, 0>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 1: dkdv_issue_copy<D, 1>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 2: dkdv_issue_copy<D, 2>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 3: dkdv_issue_copy<D, 3>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 4: dkdv_issue_copy<D, 4>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 5: dkdv_issue_copy<D, 5>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 6: dkdv_issue_copy<D, 6>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 7: dkdv_issue_copy<D, 7>(ah, q_src, do_src, vec_src, lds_stage); break;
+        default: dkdv_issue_copy<D, 8>(ah, q_src, do_src, vec_src, lds_stage); break;
+      }
+    }
+    // --- fetch the operand of step x + RD (of the next tile once this one is used up)
+    if (x + RD < NX)
+      op[x % RD] = dkdv_operand<D>(qs, x + RD, a_base, t_base0, t_base1);
+    else
+      op[x % RD] = dkdv_operand<D>(ah.nqs, x + RD - NX, a_base, t_base0, t_base1);
     // --- vector work riding along.  Vector step j = x - NST - stage handles EPS elements of
     //     block j / NST: stage A at x, stage B one step later, stage C two steps later.
     if (x == NST - 1) vec_group(0, 0);
@@ -464,23 +534,6 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   settle(b_lte);
   settle(b_uts);
   settle(b_ute);
-  // min/max over this wave's 32 keys, for the wave-level tile class
-  MinMax8 wmm;
-  {
-    int mx[4] = {b_lts, b_lte, b_uts, b_ute}, mn[4] = {b_lts, b_lte, b_uts, b_ute};
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        mx[v] = max(mx[v], __shfl_xor(mx[v], off, 64));
-        mn[v] = min(mn[v], __shfl_xor(mn[v], off, 64));
-      }
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      wmm.v[2 * v] = __builtin_amdgcn_readfirstlane(mx[v]);
-      wmm.v[2 * v + 1] = __builtin_amdgcn_readfirstlane(mn[v]);
-    }
-  }
   const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
 
   f32x16 dkacc[NDB], dvacc[NDB];
@@ -501,58 +554,64 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const int t_base0 = C::L::off(4 * g + (i16 >> 2), (16 * half + 4 * (i16 & 3)) * 2);
   const int t_base1 = C::L::off(4 * g + (i16 >> 2) + 8, (16 * half + 4 * (i16 & 3)) * 2);
   const int lane_src = async_src_offset<D>(wave, lane);
-  // wave 0 also copies the tile's lse and D slices: lanes 0-15 lse, lanes 16-31 D, 16 bytes each
-  const float* my_vec = ((lane & 16) ? dvp : lsep) + (lane & 15) * 4;
+  // every wave copies its 16 rows of the tile's lse and D slices with lanes 0..7:
+  // lanes 0-3 lse, lanes 4-7 D, 16 bytes each
+  const float* my_vec = ((lane & 4) ? dvp : lsep) + wave * 16 + (lane & 3) * 4;
+  const unsigned lds_ring = lds_address(smem + C::STAGE_OFF);
 
-#define FM_LOAD_TILE(ENTRY, BUF)                                                                 \
-  {                                                                                              \
-    const int i_ = (ENTRY) & 0xFFFFFF;                                                           \
-    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                          \
-    tile_load_async<D, QT>(qp + (size_t)i_ * QT * D, lane_src, st_, wave);                       \
-    tile_load_async<D, QT>(dop + (size_t)i_ * QT * D, lane_src, st_ + C::Q_BYTES, wave);         \
-    if (wave == 0 && lane < 32) async_copy16(my_vec + i_ * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES)); \
-  }
+  DkdvAhead ah;
+  ah.q_base = (const char*)qp;
+  ah.do_base = (const char*)dop;
+  ah.vec_src = my_vec;
+  ah.lds_ring = lds_ring;
+  ah.lane_off = (unsigned)lane_src * 2;
+  ah.wave = wave;
+  bf16x8 op[C::RD];
 
   // One pass of the tile loop over list entries [T0, T1) with the element mask compiled in or
   // out.  Tiles that need no element mask are listed first and run through the mask-free
   // instantiation, partially masked ones (for the workgroup's 128 keys) through the other;
   // keeping the two instantiations in separate loops keeps the 128 accumulator registers where
   // they are (merged into one loop, the compiler shuffled all of them every tile).
+  // Entries past the end of the list are clamped to the last one: the copies and operand
+  // fetches made for them are never used, and every entry costs the same number of copies.
 #define FM_TILE_LOOP(T0, T1, MASKED)                                                                   \
   for (int t = (T0); t < (T1); ++t) {                                                                  \
-    /* tile t has landed once at most min(NSTAGE - 2, tiles after t) later copies are in flight */     \
-    wait_tile_landed<C::COPIES>(min(C::NSTAGE - 2, n_live - 1 - t), wave == 0);                        \
-    barrier_nofence(); /* every wave's part of tile t is in LDS; every wave is done with tile t-1 */   \
-    if (t + C::NSTAGE - 1 < n_live) {                                                                  \
-      const int e = __builtin_amdgcn_readfirstlane(list[t + C::NSTAGE - 1]);                           \
-      FM_LOAD_TILE(e, (t + C::NSTAGE - 1) % C::NSTAGE);                                                \
-    }                                                                                                  \
-    const int i_blk = __builtin_amdgcn_readfirstlane(list[t]) & 0xFFFFFF;                              \
+    const int v_next = list[min(t + 1, n_live - 1)];                                                   \
+    ah.v_copy = list[min(t + C::NSTAGE - 1, n_live - 1)];                                              \
+    ah.nqs = smem + C::STAGE_OFF + ((t + 1) % C::NSTAGE) * C::STAGE;                                   \
+    ah.stage_copy = (t + C::NSTAGE - 1) % C::NSTAGE;                                                   \
     const char* st = smem + C::STAGE_OFF + (t % C::NSTAGE) * C::STAGE;                                 \
-    const float* lse_s = (const float*)(st + C::Q_BYTES + C::DO_BYTES);                                \
-    const int r0 = i_blk * QT;                                                                         \
-    if (classify_tile(r0, min(r0 + QT, N), wmm) != T_FULLY)                                            \
-      dkdv_tile<D, MASKED>(st, st + C::Q_BYTES, lse_s, lse_s + QT, kreg, vreg, dkacc, dvacc, a_base,   \
-                           t_base0, t_base1, r0, g, sc, b_lts, b_lte, b_uts, b_ute);                   \
+    const int r0 = (e_cur & 0xFFFFFF) * QT;                                                            \
+    dkdv_tile<D, MASKED>(st, (const float*)(st + C::Q_BYTES + C::DO_BYTES), ah, op, kreg, vreg, dkacc, dvacc, \
+                         a_base, t_base0, t_base1, r0, g, sc, b_lts, b_lte, b_uts, b_ute);             \
+    e_cur = __builtin_amdgcn_readfirstlane(v_next);                                                    \
   }
 
   for (int chunk = 0; chunk < t_r; chunk += C::LIST_CAP) {
     int n_plain = 0;
     const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, t_r), list, wave_cnt, n_plain);
     if (n_live == 0) continue;
-    // prologue: copies of the first NSTAGE - 1 tiles
+    // prologue: copies of the first NSTAGE - 1 tiles, then the first tile's first operands
 #pragma unroll
-    for (int p = 0; p < C::NSTAGE - 1; ++p)
-      if (p < n_live) {
-        const int e = __builtin_amdgcn_readfirstlane(list[p]);
-        FM_LOAD_TILE(e, p);
-      }
+    for (int p = 0; p < C::NSTAGE - 1; ++p) {
+      const int i_p = __builtin_amdgcn_readfirstlane(list[min(p, n_live - 1)]) & 0xFFFFFF;
+      char* st_ = smem + C::STAGE_OFF + p * C::STAGE;
+      tile_load_async<D, QT>(qp + (size_t)i_p * QT * D, lane_src, st_, wave);
+      tile_load_async<D, QT>(dop + (size_t)i_p * QT * D, lane_src, st_ + C::Q_BYTES, wave);
+      async_copy16_lanes8(my_vec + i_p * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES) + wave * 128);
+    }
+    async_wait<(C::NSTAGE - 2) * C::NC>();
+    barrier_nofence();
+    int e_cur = __builtin_amdgcn_readfirstlane(list[0]);
+#pragma unroll
+    for (int x = 0; x < C::RD; ++x) op[x] = dkdv_operand<D>(smem + C::STAGE_OFF, x, a_base, t_base0, t_base1);
     FM_TILE_LOOP(0, n_plain, false)
     FM_TILE_LOOP(n_plain, n_live, true)
+    async_wait<0>();   // the copies made for entries past the end must not outlive the list / the workgroup
     __syncthreads();   // the list and the ring are rebuilt by the next chunk
   }
 #undef FM_TILE_LOOP
-#undef FM_LOAD_TILE
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
   __bf16* dkp = (__bf16*)a.dk + (size_t)bh * N * D;

@@ -140,6 +140,24 @@ __device__ __forceinline__ void async_copy16(const void* gsrc, unsigned lds_addr
                : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gsrc)
                : "memory", "m0");
 }
+// Same copy with the global address given as a wave-uniform base (scalar registers) plus a
+// 32-bit per-lane byte offset: no per-copy vector address arithmetic.
+__device__ __forceinline__ void async_copy16_sbase(const void* uniform_base, unsigned lane_byte_off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_byte_off), "s"(uniform_base)
+               : "memory", "m0");
+}
+// Copy by lanes 0..7 only (128 bytes to lds_addr), whatever the wave's execution mask is;
+// the mask is narrowed and restored inside the statement, so no branch is needed around it.
+__device__ __forceinline__ void async_copy16_lanes8(const void* gsrc, unsigned lds_addr) {
+  unsigned long long saved;
+  asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xff\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %2, off\n\ts_mov_b64 exec, %0"
+               : "=&s"(saved)
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gsrc)
+               : "memory", "m0");
+}
 __device__ __forceinline__ unsigned lds_address(const void* lds_generic) {
   return (unsigned)(size_t)((FM_LDS const char*)lds_generic);
 }
