@@ -16,6 +16,7 @@ FLAGS = [
     # the tile loops are written as fully unrolled step sequences (#pragma unroll over
     # compile-time schedules); the default size cap on pragma-driven unrolling is too small
     "-mllvm", "-pragma-unroll-threshold=1000000",
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

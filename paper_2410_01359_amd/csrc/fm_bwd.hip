@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     if (which == 3) p = a.ute;
     my_bvec = p + (size_t)b * N + (lane & 15) * 4;
   }
-  const int lane_src = async_src_offset<D>(wave, lane);
+  CopyLanes<D> copy_lanes;
+  copy_lanes.init(lane);
 
   bf16x8 qreg[NKK], doreg[NKK];
 #pragma unroll
@@ -135,8 +136,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   {                                                                                            \
     const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
-    tile_load_async<D, KT>(kp + (size_t)j_ * KT * D, lane_src, st_, wave);                     \
-    tile_load_async<D, KT>(vp + (size_t)j_ * KT * D, lane_src, st_ + C::K_BYTES, wave);        \
+    tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                     \
+    tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_ + C::K_BYTES, wave);        \
     if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
   }
@@ -323,7 +324,7 @@ struct DkdvAhead {
   const float* vec_src;
   unsigned lds_ring;      // LDS address of stage 0
   unsigned stage_copy;    // index of the stage that receives the copy
-  unsigned lane_off;      // this lane's byte offset inside a 4 KB copy group
+  CopyLanes<128> lanes;   // per-lane source offsets of the copy instructions (the first D/32 entries are used)
   int wave;
 };
 
@@ -333,13 +334,16 @@ __device__ __forceinline__ void dkdv_issue_copy(const DkdvAhead& ah, const char*
                                                 const float* vec_src, unsigned lds_stage) {
   using C = DkdvCfg<D>;
   constexpr int HALF = C::COPIES / 2;
-  if (K < HALF)
-    async_copy16_sbase(q_src + K * 4096, ah.lane_off, lds_stage + ah.wave * 1024 + K * 4096);
-  else if (K < C::COPIES)
-    async_copy16_sbase(do_src + (K - HALF) * 4096, ah.lane_off,
-                       lds_stage + C::Q_BYTES + ah.wave * 1024 + (K - HALF) * 4096);
-  else
+  constexpr int WB = 16 * C::L::RS;   // bytes of a wave's 16-row block
+  if (K < HALF) {
+    if (K == 0) async_window(lds_stage + ah.wave * WB);
+    async_copy16_window<(K % HALF) * 1024>(q_src + ah.wave * WB, ah.lanes.v[K % HALF]);
+  } else if (K < C::COPIES) {
+    if (K == HALF) async_window(lds_stage + C::Q_BYTES + ah.wave * WB);
+    async_copy16_window<(K % HALF) * 1024>(do_src + ah.wave * WB, ah.lanes.v[K % HALF]);
+  } else {
     async_copy16_lanes8(vec_src, lds_stage + C::Q_BYTES + C::DO_BYTES + ah.wave * 128);
+  }
 }
 
 // LDS operand of step x of the tile whose Q tile starts at qs (dO tile right behind it)
@@ -553,7 +557,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const int a_base = C::L::off(c, 16 * g);
   const int t_base0 = C::L::off(4 * g + (i16 >> 2), (16 * half + 4 * (i16 & 3)) * 2);
   const int t_base1 = C::L::off(4 * g + (i16 >> 2) + 8, (16 * half + 4 * (i16 & 3)) * 2);
-  const int lane_src = async_src_offset<D>(wave, lane);
+  CopyLanes<D> copy_lanes;
+  copy_lanes.init(lane);
   // every wave copies its 16 rows of the tile's lse and D slices with lanes 0..7:
   // lanes 0-3 lse, lanes 4-7 D, 16 bytes each
   const float* my_vec = ((lane & 4) ? dvp : lsep) + wave * 16 + (lane & 3) * 4;
@@ -564,7 +569,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   ah.do_base = (const char*)dop;
   ah.vec_src = my_vec;
   ah.lds_ring = lds_ring;
-  ah.lane_off = (unsigned)lane_src * 2;
+#pragma unroll
+  for (int s = 0; s < CopyLanes<D>::NINST; ++s) ah.lanes.v[s] = copy_lanes.v[s];
   ah.wave = wave;
   bf16x8 op[C::RD];
 
@@ -597,8 +603,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     for (int p = 0; p < C::NSTAGE - 1; ++p) {
       const int i_p = __builtin_amdgcn_readfirstlane(list[min(p, n_live - 1)]) & 0xFFFFFF;
       char* st_ = smem + C::STAGE_OFF + p * C::STAGE;
-      tile_load_async<D, QT>(qp + (size_t)i_p * QT * D, lane_src, st_, wave);
-      tile_load_async<D, QT>(dop + (size_t)i_p * QT * D, lane_src, st_ + C::Q_BYTES, wave);
+      tile_load_async<D>(qp + (size_t)i_p * QT * D, copy_lanes, st_, wave);
+      tile_load_async<D>(dop + (size_t)i_p * QT * D, copy_lanes, st_ + C::Q_BYTES, wave);
       async_copy16_lanes8(my_vec + i_p * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES) + wave * 128);
     }
     async_wait<(C::NSTAGE - 2) * C::NC>();

@@ -112,19 +112,31 @@ struct TileLayout {
   static __device__ __forceinline__ int add_col(int base, int colc) { return base ^ colc; }
 };
 
-// Asynchronous global->LDS copy of a [ROWS][D] bf16 tile (global row stride D)
-// into TileLayout<D> order by a 256-thread workgroup.  Every wave instruction
-// moves 64 x 16 B = 1 KB straight into LDS (no staging registers); the
-// swizzle is applied on the global-address side.  `lane_src` is this thread's
-// element offset from async_src_offset(); completion is awaited by the
-// vmcnt(0) that precedes the next workgroup barrier.
+// Asynchronous global->LDS copy of a [64][D] bf16 tile (global row stride D)
+// into TileLayout<D> order by a 4-wave workgroup.  Wave w copies rows
+// 16w..16w+15, a contiguous block on both sides, with NINST instructions of
+// 64 x 16 B = 1 KB each straight into LDS (no staging registers); the swizzle is
+// applied on the global-address side.  The LDS destination of such an
+// instruction is M0 + immediate offset + 16 * lane and the same immediate is
+// added to the global address, so one M0 value (async_window) serves all of a
+// wave's instructions for a tile: rewriting M0 costs the issuing wave about as
+// much as the copy itself.  CopyLanes holds the per-lane source byte offset
+// of each instruction (relative to the wave's row block); the swizzle repeats
+// every 16 rows, so it does not depend on the wave.
 template <int D>
-__device__ __forceinline__ int async_src_offset(int wave, int lane) {
+struct CopyLanes {
   using L = TileLayout<D>;
-  constexpr int RPI = 64 / L::CPR;                    // rows per wave instruction
-  const int row = wave * RPI + lane / L::CPR;         // row within the first 4 KB; swizzle repeats every 16 rows
-  return row * D + (((lane % L::CPR) ^ L::swz(row)) << 3);
-}
+  static constexpr int RPI = 64 / L::CPR;     // rows per instruction
+  static constexpr int NINST = 16 / RPI;      // instructions per wave and tile
+  unsigned v[NINST];
+  __device__ __forceinline__ void init(int lane) {
+#pragma unroll
+    for (int s = 0; s < NINST; ++s) {
+      const int row = lane / L::CPR;          // row within the instruction's 1 KB
+      v[s] = row * L::RS + (((lane % L::CPR) ^ L::swz(s * RPI + row)) << 4);
+    }
+  }
+};
 // One wave-wide asynchronous copy: every active lane moves 16 bytes from its own
 // global address to LDS address lds_addr + 16 * lane (lds_addr wave-uniform).
 // Issued through inline assembly on purpose: the compiler treats the builtin
@@ -177,14 +189,36 @@ __device__ __forceinline__ void barrier_nofence() {
   asm volatile("" ::: "memory");
 }
 
-template <int D, int ROWS>
-__device__ __forceinline__ void tile_load_async(const __bf16* tile_src, int lane_src, char* lds_tile, int wave) {
-  using L = TileLayout<D>;
-  constexpr int RPI = 64 / L::CPR;
-  constexpr int NINST = ROWS / RPI / 4;
-  const unsigned base = lds_address(lds_tile) + wave * 1024;
-#pragma unroll
-  for (int s = 0; s < NINST; ++s) async_copy16(tile_src + s * 4 * RPI * D + lane_src, base + s * 4096);
+// Set the LDS window (M0) of the async_copy16_window copies that follow.  M0 is
+// not otherwise used by these kernels; the window stays valid until the next
+// async_window / async_copy16* call.
+__device__ __forceinline__ void async_window(unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
+}
+// One wave-wide copy inside the current window: lane l moves 16 bytes from
+// uniform_base + lane_byte_off + IMM to LDS address M0 + IMM + 16 l.
+template <int IMM>
+__device__ __forceinline__ void async_copy16_window(const void* uniform_base, unsigned lane_byte_off) {
+  static_assert(IMM >= 0 && IMM < 4096, "immediate offset range");
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(lane_byte_off), "s"(uniform_base), "n"(IMM) : "memory");
+}
+// Instruction S (of CopyLanes<D>::NINST) of a wave's part of a tile copy.
+template <int D, int S>
+__device__ __forceinline__ void tile_copy_inst(const void* wave_src, const CopyLanes<D>& cl) {
+  async_copy16_window<S * 1024>(wave_src, cl.v[S]);
+}
+// A wave's whole part of a [64][D] tile copy: tile_src / lds_tile are the tile's first row.
+template <int D>
+__device__ __forceinline__ void tile_load_async(const __bf16* tile_src, const CopyLanes<D>& cl, const char* lds_tile,
+                                                int wave) {
+  const char* wave_src = (const char*)tile_src + wave * 16 * TileLayout<D>::RS;
+  async_window(lds_address(lds_tile) + wave * 16 * TileLayout<D>::RS);
+  tile_copy_inst<D, 0>(wave_src, cl);
+  tile_copy_inst<D, 1>(wave_src, cl);
+  if (CopyLanes<D>::NINST == 4) {
+    tile_copy_inst<D, 2>(wave_src, cl);
+    tile_copy_inst<D, 3>(wave_src, cl);
+  }
 }
 
 // Force a value that was fetched with an ordinary global load to be complete

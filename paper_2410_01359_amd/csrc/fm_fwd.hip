@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
     if (which == 3) p = a.ute;
     my_bvec = p + (size_t)b * N + (lane & 15) * 4;
   }
-  const int lane_src = async_src_offset<D>(wave, lane);
+  CopyLanes<D> copy_lanes;
+  copy_lanes.init(lane);
 
   // Q fragments (B operand of S^T = K Q^T): lane holds Q[row c][16 kk + 8 g ..+7].
   bf16x8 qreg[QB][NKK];
@@ -115,8 +116,8 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
   {                                                                                            \
     const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
-    tile_load_async<D, KT>(kp + (size_t)j_ * KT * D, lane_src, st_, wave);                     \
-    tile_load_async<D, KT>(vp + (size_t)j_ * KT * D, lane_src, st_ + C::K_BYTES, wave);        \
+    tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                     \
+    tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_ + C::K_BYTES, wave);        \
     if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
   }
