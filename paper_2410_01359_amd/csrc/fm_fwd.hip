@@ -1,7 +1,7 @@
 // Forward tile loop (Algorithm 1) for gfx950.
 //
-// One workgroup (4 waves) per (batch, head, block of BR query rows).  Each wave
-// owns 32*QB query rows for the whole kernel and walks the key blocks that the
+// One workgroup (4 waves) per (batch, head, block of 128 query rows).  Each wave
+// owns 32 query rows for the whole kernel and walks the key blocks that the
 // min/max tables do not prove fully masked.  Scores are computed transposed,
 // S^T = K Q^T, so that after the MFMA every lane holds ONE query column: row
 // max / row sum are per-lane loops plus one exchange with the lane 32 away, the
@@ -9,31 +9,164 @@
 // B-operand layout of the second product O^T += V^T P^T.  K tiles are read
 // from LDS as A operands (128-bit reads), V tiles through the LDS transpose
 // read.  Q stays in registers.
+//
+// The loop is software-pipelined over key tiles: while the exp / row-sum
+// arithmetic of tile t runs on the vector unit, the matrix unit already computes
+// the scores of tile t+1 into a second accumulator set, so a wave keeps both
+// units busy by itself instead of relying on the other resident wave being in
+// the complementary phase.  K and V therefore travel in separate two-deep LDS
+// rings: iteration t reads K(t+1) and V(t) while K(t+2) and V(t+1) are in flight.
 #include "fm_common.h"
 #include "fm_kernels.h"
 
 namespace fm {
 
-template <int D, int QB>
+template <int D>
 struct FwdCfg {
   static constexpr int KT = FM_FWD_BC;          // keys per tile
-  static constexpr int BR = 128 * QB;           // query rows per workgroup
-  using L = TileLayout<D>;                      // swizzled / padded LDS rows
+  static constexpr int BR = FM_FWD_BR;          // query rows per workgroup
+  using L = TileLayout<D>;
   static constexpr int K_BYTES = KT * L::RS;
   static constexpr int V_BYTES = KT * L::RS;
-  static constexpr int BND_BYTES = 4 * KT * 4;  // LTS, LTE, UTS, UTE slices of one tile
-  static constexpr int STAGE = K_BYTES + V_BYTES + BND_BYTES;
+  static constexpr int BND_BYTES = 4 * KT * 4;  // LTS, LTE, UTS, UTE slices of one tile, kept behind its V tile
+  static constexpr int VSTAGE = V_BYTES + BND_BYTES;
   static constexpr int LIST_CAP = 1024;         // key blocks classified per pass
   static constexpr int LIST_OFF = 0;
   static constexpr int CNT_OFF = LIST_CAP * 4;
-  static constexpr int STAGE_OFF = CNT_OFF + 64;
-  static constexpr int LDS_BYTES = STAGE_OFF + 2 * STAGE;
+  static constexpr int K_OFF = CNT_OFF + 64;
+  static constexpr int V_OFF = K_OFF + 2 * K_BYTES;
+  static constexpr int LDS_BYTES = V_OFF + 2 * VSTAGE;
 };
 
-template <int D, int QB>
-__global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) {
-  using C = FwdCfg<D, QB>;
+// Per-wave constants of the tile loop.
+template <int D>
+struct FwdWave {
+  int a_off;               // operand rows: row c, bytes 16 g (slice kk adds 32 kk through TileLayout::add_col)
+  int t_off[2];            // transpose reads: row 4 g + i16/4 (+8), bytes 32 half + 8 (i16 & 3) (d block db adds 64 db)
+  int row;                 // this lane's query row
+  int g;
+  float sc;                // scale * log2(e)
+};
+
+// One pipeline step: exp / row-sum arithmetic and O^T += V^T P^T of the tile whose raw scores
+// are in `cur` (masked first if `masked`), and the raw scores of the NEXT tile (K tile at
+// k_next) into `nxt`.
+template <int D>
+__device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32x16 (&oacc)[D / 32],
+                                         const bf16x8 (&qreg)[D / 16], float& m_run, float& l_run,
+                                         const char* k_next, const char* vs, const int* bnd, bool masked,
+                                         const FwdWave<D>& w) {
+  using C = FwdCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
+  static_assert(NKB == 2, "two 32-key blocks per tile");
+  constexpr float kRescaleGap = 8.f;
+  // per-lane LDS offsets, made opaque once per tile so that what is derived from them is
+  // recomputed (one vector op each) instead of being hoisted out of the tile loop into registers
+  const int a_b = opaque(w.a_off), t_b0 = opaque(w.t_off[0]), t_b1 = opaque(w.t_off[1]);
+
+  if (masked) {
+    const int* bnd_g = (const int*)((const char*)bnd + opaque(16 * w.g));
+    // Both pairs are applied whenever the wave's sub-tile is not mask-free: a pair whose
+    // NEED bit is clear masks no element of this tile, so this is exact.  A sub-tile that
+    // Equation 4 proves fully masked takes the same path and ends with every score at -inf.
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int kx = kb * 32 + 8 * rq;
+        const i32x4 bl = *(const i32x4*)(bnd_g + 0 * KT + kx);
+        const i32x4 be = *(const i32x4*)(bnd_g + 1 * KT + kx);
+        const i32x4 bu = *(const i32x4*)(bnd_g + 2 * KT + kx);
+        const i32x4 bv = *(const i32x4*)(bnd_g + 3 * KT + kx);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool hit = ((w.row >= bl[e]) & (w.row < be[e])) | ((w.row >= bu[e]) & (w.row < bv[e]));
+          if (hit) cur[kb][rq * 4 + e] = -INFINITY;
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the bound reads of later steps from piling up in registers
+      }
+  }
+
+  // ---- stream A: S^T(next) = K Q^T on the matrix unit, softmax(cur) on the vector unit.
+  // MFMA step n: chain kb = n % 2, slice kk = n / 2 (the two accumulation chains alternate);
+  // its K operand is fetched RS steps ahead into a small register ring.
+  constexpr int NS = NKB * NKK, RS = 4;
+  constexpr int NMAX = 4;                          // steps that carry the running max (8 elements each)
+  constexpr int NEXP = NS - NMAX - 1;              // steps that carry the exponentials
+  constexpr int EPS = (32 + NEXP - 1) / NEXP;      // elements per such step
+  bf16x8 kring[RS];
+  auto k_operand = [&](int n) __attribute__((always_inline)) {
+    return *(const bf16x8*)(k_next + (n % NKB) * 32 * C::L::RS + C::L::add_col(a_b, (n / NKB) * 32));
+  };
+  const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int n = 0; n < RS; ++n) kring[n] = k_operand(n);
+  __builtin_amdgcn_sched_barrier(0);
+  float mx = -INFINITY, neg_m = 0.f, rs = 0.f;
+#pragma unroll
+  for (int n = 0; n < NS; ++n) {
+    nxt[n % NKB] = mfma32(kring[n % RS], qreg[n / NKB], n < NKB ? zero : nxt[n % NKB]);
+    if (n + RS < NS) kring[n % RS] = k_operand(n + RS);
+    if (n < NMAX) {
+#pragma unroll
+      for (int e = 8 * n; e < 8 * n + 8; ++e) mx = fmaxf(mx, cur[e / 16][e % 16]);
+    } else if (n == NMAX) {
+      mx = fmaxf(mx, partner32(mx)) * w.sc;
+      const bool grow = mx > m_run + kRescaleGap;   // also true on the first finite maximum
+      if (__any(grow)) {
+        // The reference maximum only moves when a tile's maximum exceeds it by more than the
+        // gap (log2 units), so this rescale of O and l is rare; any reference is a valid one,
+        // P just grows up to 2^gap.
+        const float m_new = grow ? mx : m_run;
+        const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      }
+      neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+    } else {
+      const int j = n - NMAX - 1;
+#pragma unroll
+      for (int e = j * EPS; e < (j + 1) * EPS && e < 32; ++e) {
+        const float p = fast_exp2(__builtin_fmaf(cur[e / 16][e % 16], w.sc, neg_m));
+        cur[e / 16][e % 16] = p;
+        rs += p;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  l_run += rs;
+
+  // ---- stream B: O^T += V^T P^T, step n = (16-key group n / NDB, d block n % NDB)
+  constexpr int NP = NKB * 2 * NDB, RP = 4;
+  bf16x8 vring[RP];
+  auto v_operand = [&](int n) __attribute__((always_inline)) {
+    const char* vrow = vs + ((n / NDB) * 16) * C::L::RS;   // group n / NDB = (kb, h): 16 keys each
+    return cat4(lds_read_tr16(vrow + C::L::add_col(t_b0, (n % NDB) * 64)),
+                lds_read_tr16(vrow + C::L::add_col(t_b1, (n % NDB) * 64)));
+  };
+#pragma unroll
+  for (int n = 0; n < RP; ++n) vring[n] = v_operand(n);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int n = 0; n < NP; ++n) {
+    const int grp = n / NDB, kb = grp / 2, h = grp % 2, db = n % NDB;
+    bf16x8 pb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pb[e] = (__bf16)cur[kb][8 * h + e];
+    oacc[db] = mfma32(vring[n % RP], pb, oacc[db]);
+    if (n + RP < NP) vring[n % RP] = v_operand(n + RP);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
+  using C = FwdCfg<D>;
+  constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16, QB = 1;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int unit = a.order[blockIdx.x];
@@ -45,7 +178,7 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
   const int t_r = N / C::BR, t_c = N / KT;
   const int bh = unit / t_r, i_blk = unit - bh * t_r, b = bh / H;
   const int q0 = i_blk * C::BR;
-  const int qw0 = q0 + wave * 32 * QB;
+  const int qw0 = q0 + wave * 32;
 
   const __bf16* qp = (const __bf16*)a.q + (size_t)bh * N * D;
   const __bf16* kp = (const __bf16*)a.k + (size_t)bh * N * D;
@@ -66,208 +199,104 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
   copy_lanes.init(lane);
 
   // Q fragments (B operand of S^T = K Q^T): lane holds Q[row c][16 kk + 8 g ..+7].
-  bf16x8 qreg[QB][NKK];
+  bf16x8 qreg[NKK];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+  for (int kk = 0; kk < NKK; ++kk) qreg[kk] = *(const bf16x8*)(qp + (size_t)(qw0 + c) * D + kk * 16 + 8 * g);
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk)
-      qreg[qb][kk] = *(const bf16x8*)(qp + (size_t)(qw0 + qb * 32 + c) * D + kk * 16 + 8 * g);
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) settle(qreg[qb][kk]);
+  for (int kk = 0; kk < NKK; ++kk) settle(qreg[kk]);
 
-  f32x16 oacc[NDB][QB];
-  float m_run[QB], l_run[QB];
+  f32x16 oacc[NDB];
+  float m_run = -INFINITY, l_run = 0.f;   // log2 domain
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
+  for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
-  }
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 
   int* list = (int*)(smem + C::LIST_OFF);
   int* wave_cnt = (int*)(smem + C::CNT_OFF);
-  const float sc = a.scale * kLog2e;  // > 0 (checked on the host)
-  // Scores stay raw; exp2(s*sc - m) is one fma + one exp.  The reference
-  // maximum m only moves when a tile's maximum exceeds it by more than
-  // kRescaleGap (log2 units), so the rescale of O and l is rare; any m is a
-  // valid softmax reference, P just grows up to 2^kRescaleGap.
-  constexpr float kRescaleGap = 8.f;
+  FwdWave<D> w;
+  w.sc = a.scale * kLog2e;  // > 0 (checked on the host): scores stay raw, exp2(s*sc - m) is one fma + one exp
+  w.row = qw0 + c;
+  w.g = g;
+  {
+    const int i16 = lane & 15, half = (lane >> 4) & 1;
+    w.a_off = C::L::off(c, 16 * g);
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) w.t_off[hi] = C::L::off(4 * g + (i16 >> 2) + 8 * hi, (16 * half + 4 * (i16 & 3)) * 2);
+  }
 
-  // lane-dependent LDS offsets inside a tile (row block 0)
-  const int i16 = lane & 15, half = (lane >> 4) & 1;
-  int a_off[NKK];       // operand rows: row c, bytes (16 kk + 8 g) * 2
-  int t_off[2][NDB];    // transpose reads: row 4 g + i16/4 (+8), bytes (32 db + 16 half + 4 (i16 & 3)) * 2
-#pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) a_off[kk] = C::L::off(c, (kk * 16 + 8 * g) * 2);
-#pragma unroll
-  for (int hi = 0; hi < 2; ++hi)
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-      t_off[hi][db] = C::L::off(4 * g + (i16 >> 2) + 8 * hi, (db * 32 + 16 * half + 4 * (i16 & 3)) * 2);
-
-  // Asynchronous copy of one live tile (K, V and, if partially masked, its bound slices)
-  // into stage buffer BUF; awaited by async_wait<0>() in front of the next barrier.
-#define FM_LOAD_TILE(ENTRY, BUF)                                                               \
-  {                                                                                            \
-    const int j_ = entry_block(ENTRY, chunk);                                                  \
-    char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
-    tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                     \
-    tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_ + C::K_BYTES, wave);        \
-    if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
-      async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
+  // Asynchronous copies of list entry ENTRY: its K tile into K stage KBUF / its V tile (and, if the
+  // workgroup's tile is partially masked, its bound slices) into V stage VBUF.
+#define FM_LOAD_K(ENTRY, KBUF) \
+  tile_load_async<D>(kp + (size_t)entry_block(ENTRY, chunk) * KT * D, copy_lanes, smem + C::K_OFF + (KBUF) * C::K_BYTES, wave)
+#define FM_LOAD_V(ENTRY, VBUF)                                                                   \
+  {                                                                                              \
+    const int j_ = entry_block(ENTRY, chunk);                                                    \
+    char* st_ = smem + C::V_OFF + (VBUF) * C::VSTAGE;                                            \
+    tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                         \
+    if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                       \
+      async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::V_BYTES));                            \
+  }
+  // One iteration: tile T with scores in CUR, scores of tile T + 1 into NXT.  Entries past the
+  // end of the list are clamped to the last one; what is computed from them is never used.
+#define FM_STEP(T, CUR, NXT)                                                                     \
+  {                                                                                              \
+    const int e_t = __builtin_amdgcn_readfirstlane(list[T]);                                     \
+    const int e_1 = __builtin_amdgcn_readfirstlane(list[min((T) + 1, n_live - 1)]);              \
+    const int e_2 = __builtin_amdgcn_readfirstlane(list[min((T) + 2, n_live - 1)]);              \
+    FM_LOAD_K(e_2, (T) & 1);                                                                     \
+    FM_LOAD_V(e_1, ((T) + 1) & 1);                                                               \
+    const char* vs_ = smem + C::V_OFF + ((T) & 1) * C::VSTAGE;                                   \
+    fwd_step<D>(CUR, NXT, oacc, qreg, m_run, l_run, smem + C::K_OFF + (((T) + 1) & 1) * C::K_BYTES, vs_, \
+                (const int*)(vs_ + C::V_BYTES), entry_wave_class(e_t, wave) != T_UNMASKED, w);   \
+    async_wait<0>();   /* K(T+2) and V(T+1) have landed ... */                                   \
+    barrier_nofence(); /* ... for every wave, and every wave is done with K(T+1) and V(T) */     \
   }
 
   for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
-    const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
-    FM_LOAD_TILE(first_entry, 0);
-    async_wait<0>();
-    barrier_nofence();
-
-    for (int t = 0; t < n_live; ++t) {
-      const int entry = __builtin_amdgcn_readfirstlane(list[t]);
-      const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
-      if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
-
-      const char* st = smem + C::STAGE_OFF + (t & 1) * C::STAGE;
-      const char* ks = st;
-      const char* vs = st + C::K_BYTES;
-      const int* bnd = (const int*)(st + C::K_BYTES + C::V_BYTES);
-
-      const int wcls = entry_wave_class(entry, wave);   // Equation 4 on this wave's own rows
-      if (wcls != T_FULLY) {
-        f32x16 sacc[NKB][QB];
+    {
+      const int e_0 = __builtin_amdgcn_readfirstlane(list[0]);
+      const int e_1 = __builtin_amdgcn_readfirstlane(list[min(1, n_live - 1)]);
+      FM_LOAD_K(e_0, 0);
+      FM_LOAD_V(e_0, 0);
+      FM_LOAD_K(e_1, 1);
+      async_wait<0>();
+      barrier_nofence();
+    }
+    // scores of the first tile
+    f32x16 s0[NKB], s1[NKB];
+    {
+      const char* ks = smem + C::K_OFF;
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s0[kb][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
-        // S^T = K Q^T.  The K operand of step n (chain kb = n % NKB, slice kk = n / NKB: the
-        // accumulation chains alternate) is fetched RS steps ahead into a small register ring,
-        // so an MFMA never waits for a read issued just before it.
-        constexpr int NS = NKB * NKK, RS = 6;
-        bf16x8 kring[RS];
-        auto k_operand = [&](int n) __attribute__((always_inline)) {
-          return *(const bf16x8*)(ks + (n % NKB) * 32 * C::L::RS + a_off[n / NKB]);
-        };
-#pragma unroll
-        for (int n = 0; n < RS; ++n) kring[n] = k_operand(n);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int n = 0; n < NS; ++n) {
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            sacc[n % NKB][qb] = mfma32(kring[n % RS], qreg[qb][n / NKB], sacc[n % NKB][qb]);
-          if (n + RS < NS) kring[n % RS] = k_operand(n + RS);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        // The V operands of the second product do not depend on the scores: start fetching them
-        // now, so they arrive while the softmax arithmetic runs.
-        constexpr int NP = NKB * 2 * NDB, RP = 4;
-        bf16x8 vring[RP];
-        auto v_operand = [&](int n) __attribute__((always_inline)) {
-          const char* vrow = vs + ((n / NDB) * 16) * C::L::RS;   // group n / NDB = (kb, h): 16 keys each
-          return cat4(lds_read_tr16(vrow + t_off[0][n % NDB]), lds_read_tr16(vrow + t_off[1][n % NDB]));
-        };
-#pragma unroll
-        for (int n = 0; n < RP; ++n) vring[n] = v_operand(n);
-        __builtin_amdgcn_sched_barrier(0);
-        if (wcls & T_PARTIAL) {
-          // Both pairs are applied whenever the tile is partial: a pair whose
-          // NEED bit is clear masks no element of this tile, so this is exact,
-          // and branch-free code here keeps the register allocation sane.
-#pragma unroll
-          for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-              const int kx = kb * 32 + 8 * rq + 4 * g;
-              const i32x4 bl = *(const i32x4*)(bnd + 0 * KT + kx);
-              const i32x4 be = *(const i32x4*)(bnd + 1 * KT + kx);
-              const i32x4 bu = *(const i32x4*)(bnd + 2 * KT + kx);
-              const i32x4 bv = *(const i32x4*)(bnd + 3 * KT + kx);
-#pragma unroll
-              for (int qb = 0; qb < QB; ++qb) {
-                const int row = qw0 + qb * 32 + c;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const bool masked = ((row >= bl[e]) & (row < be[e])) | ((row >= bu[e]) & (row < bv[e]));
-                  if (masked) sacc[kb][qb][rq * 4 + e] = -INFINITY;
-                }
-              }
-              __builtin_amdgcn_sched_barrier(0);  // keep the bound reads of later steps from piling up in registers
-            }
-        }
-
-        // online softmax (per lane = per query column)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          float mx = -INFINITY;
-#pragma unroll
-          for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-          mx = fmaxf(mx, partner32(mx)) * sc;
-          const bool grow = mx > m_run[qb] + kRescaleGap;   // also true on the first finite maximum
-          if (__any(grow)) {
-            const float m_new = grow ? mx : m_run[qb];
-            const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            l_run[qb] *= alpha;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-          }
-          const float neg_m = (m_run[qb] == -INFINITY) ? 0.f : -m_run[qb];
-          float rs = 0.f;
-#pragma unroll
-          for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float p = fast_exp2(__builtin_fmaf(sacc[kb][qb][r], sc, neg_m));
-              sacc[kb][qb][r] = p;
-              rs += p;
-            }
-          l_run[qb] += rs;
-        }
-
-        __builtin_amdgcn_sched_barrier(0);
-        // O^T += V^T P^T, step n = (16-key group n / NDB, d block n % NDB)
-#pragma unroll
-        for (int n = 0; n < NP; ++n) {
-          const int grp = n / NDB, kb = grp / 2, h = grp % 2, db = n % NDB;
-          bf16x8 pb[QB];
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pb[qb][e] = (__bf16)sacc[kb][qb][8 * h + e];
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(vring[n % RP], pb[qb], oacc[db][qb]);
-          if (n + RP < NP) vring[n % RP] = v_operand(n + RP);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-
-      async_wait<0>();   // the next tile has landed ...
-      barrier_nofence(); // ... for every wave, and every wave is done reading this one
+          s0[kb] = mfma32(*(const bf16x8*)(ks + kb * 32 * C::L::RS + C::L::add_col(w.a_off, kk * 32)), qreg[kk], s0[kb]);
+      barrier_nofence();   // the first iteration refills this K stage: every wave must have read it
+    }
+    for (int t = 0; t < n_live; t += 2) {
+      FM_STEP(t, s0, s1)
+      if (t + 1 < n_live) FM_STEP(t + 1, s1, s0)
     }
     __syncthreads();     // the list is rebuilt by the next pass
   }
+#undef FM_STEP
+#undef FM_LOAD_K
+#undef FM_LOAD_V
 
   // epilogue: O / l, lse = m + log(l)   (m, l in the log2 domain)
   __bf16* op = (__bf16*)a.out + (size_t)bh * N * D;
   float* lp = a.lse + (size_t)bh * N;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const float lt = l_run[qb] + partner32(l_run[qb]);
+    const float lt = l_run + partner32(l_run);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int row = qw0 + qb * 32 + c;
 #pragma unroll
@@ -276,35 +305,33 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void fwd_kernel(FmFwdArgs a) 
       for (int rq = 0; rq < 4; ++rq) {
         bf16x4 o4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][qb][rq * 4 + e] * inv);
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][rq * 4 + e] * inv);
         *(bf16x4*)(op + (size_t)row * D + db * 32 + 8 * rq + 4 * g) = o4;
       }
-    if (g == 0) lp[row] = lt > 0.f ? (m_run[qb] + fast_log2(lt)) * kLn2 : -INFINITY;
+    if (g == 0) lp[row] = lt > 0.f ? (m_run + fast_log2(lt)) * kLn2 : -INFINITY;
   }
 }
-
-#undef FM_LOAD_TILE
 
 }  // namespace fm
 
 using namespace fm;
 
-template <int D, int QB>
+template <int D>
 static hipError_t launch_fwd_t(const FmFwdArgs& a, hipStream_t stream) {
-  using C = FwdCfg<D, QB>;
+  using C = FwdCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D, QB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fwd_kernel<D, QB>), dim3(a.slots), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((fwd_kernel<D>), dim3(a.slots), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
 hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream) {
   static_assert(FM_FWD_BR == 128, "forward row block");
-  if (a.d == 128) return launch_fwd_t<128, 1>(a, stream);
-  return launch_fwd_t<64, 1>(a, stream);
+  if (a.d == 128) return launch_fwd_t<128>(a, stream);
+  return launch_fwd_t<64>(a, stream);
 }
