@@ -17,7 +17,7 @@
 namespace fm {
 
 // ---------------------------------------------------------------------------
-// D pre-pass (plus the log2-domain copy of lse the tile loops use).  One row per
+// D pre-pass: writes -D_i = -sum_c dO_ic O_ic (plus the log2-domain copy of lse the tile loops use).  One row per
 // 16 (d = 128) or 8 (d = 64) lanes, 16 bytes per lane.
 // ---------------------------------------------------------------------------
 template <int D>
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ ou
 #pragma unroll
   for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
   if (row < rows && part == 0) {
-    dvec[row] = acc;
+    dvec[row] = -acc;   // stored negated: the tile loops add it
     // lse for the backward's exponent: log2 domain, and +inf for a row with no
     // visible key (lse = -inf) so that exp2(s - lse2) is exactly 0 there
     const float l = lse[row];
@@ -108,14 +108,14 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   }
   // lse in the log2 domain (+inf for a row with no visible key, so that P = 0 there)
   float lse2 = a.lse2[(size_t)bh * N + row];
-  float dsum = a.dvec[(size_t)bh * N + row];
+  float dneg = a.dvec[(size_t)bh * N + row];   // -D of this lane's row
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
     settle(qreg[kk]);
     settle(doreg[kk]);
   }
   settle(lse2);
-  settle(dsum);
+  settle(dneg);
 
   f32x16 dqacc[NDB];
 #pragma unroll
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float p = fast_exp2(__builtin_fmaf(sacc[r], sc, -lse2));
-            sacc[r] = p * (dpacc[r] - dsum);
+            sacc[r] = p * (dpacc[r] + dneg);
           }
           __builtin_amdgcn_sched_barrier(0);
           // dQ^T += K^T dS^T
@@ -295,11 +295,12 @@ __device__ __forceinline__ constexpr int dkdv_vec_off(int r, bool d_part) {
 // tile loop issues in three consecutive steps, so that a step never holds two
 // dependent vector instructions of the same element (one wave per SIMD: nothing
 // else hides the latency of v_exp_f32 and of the AGPR reads):
-//   A: t = s*sc - lse2 (with the element mask), u = dP - D     B: p = exp2(t)     C: dS = p * u
+//   A: t = s*sc - lse2 (with the element mask)     B: p = exp2(t)     C: dS = p * (dP - D)
+// (dP - D comes straight out of the MFMA: its accumulator starts from the -D values of the rows)
 // Register r of a block is query row 8*(r/4) + 4*g + r%4.
 template <bool MASKED>
 __device__ __forceinline__ void dkdv_stage_a(const f32x16& s, const f32x16& dp, float (&t)[16],
-                                             float (&u)[16], const f32x4 (&l4)[4], const f32x4 (&d4)[4], int e0,
+                                             float (&u)[16], const f32x4 (&l4)[4], int e0,
                                              int cnt, int row_base /* r0 + 32*qb + 4*g */, float sc, int b_lts,
                                              int b_lte, int b_uts, int b_ute) {
 #pragma unroll
@@ -311,7 +312,7 @@ __device__ __forceinline__ void dkdv_stage_a(const f32x16& s, const f32x16& dp, 
       if (hit) x = -INFINITY;
     }
     t[r] = __builtin_fmaf(x, sc, -l4[r >> 2][r & 3]);
-    u[r] = dp[r] - d4[r >> 2][r & 3];
+    u[r] = dp[r];   // dP - D: the dP accumulator was started from -D
   }
 }
 
@@ -346,6 +347,22 @@ __device__ __forceinline__ void dkdv_issue_copy(const DkdvAhead& ah, const char*
   }
 }
 
+// Order of the 2*NKK score MFMAs of one 32-row block (step y): the S chain leads by NKK/2
+// steps, so the -D values the dP chain starts from have time to arrive from LDS:
+//   y < H: S   |   H <= y < 3H: dP, S alternating   |   y >= 3H: dP          (H = NKK / 2)
+template <int D>
+__device__ __forceinline__ constexpr bool dkdv_is_s(int y) {
+  constexpr int H = D / 32;
+  return y < H || (y < 3 * H && ((y - H) & 1));
+}
+template <int D>
+__device__ __forceinline__ constexpr int dkdv_kk(int y) {
+  constexpr int H = D / 32;
+  if (y < H) return y;
+  if (y < 3 * H) return ((y - H) & 1) ? H + (y - H - 1) / 2 : (y - H) / 2;
+  return H + (y - 3 * H);
+}
+
 // LDS operand of step x of the tile whose Q tile starts at qs (dO tile right behind it)
 template <int D>
 __device__ __forceinline__ bf16x8 dkdv_operand(const char* qs, int x, int a_base, int t_base0, int t_base1) {
@@ -353,9 +370,9 @@ __device__ __forceinline__ bf16x8 dkdv_operand(const char* qs, int x, int a_base
   constexpr int NKK = D / 16, NDB = D / 32, NST = 2 * NKK;
   const char* dos = qs + DkdvCfg<D>::Q_BYTES;
   if (x < 2 * NST) {             // row reads: Q or dO rows of block x / NST as MFMA A operand
-    const int qb = x / NST, kk = (x % NST) / 2;
-    const char* tile = (x & 1) ? dos : qs;
-    return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, kk * 32));
+    const int qb = x / NST;
+    const char* tile = dkdv_is_s<D>(x % NST) ? qs : dos;
+    return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, dkdv_kk<D>(x % NST) * 32));
   }
   // transpose reads: dO (even step, dV) or Q (odd step, dK) as MFMA B operand
   const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
@@ -404,12 +421,11 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
 
   f32x16 sb[2], pb[2];             // S then P, dP then dS, of the two blocks
   bf16x8 pa[2][2], dsa[2][2];      // bf16 P^T and dS^T, [block][16-row half]
-  f32x4 l4[2][4], d4[2][4];        // lse (log2 domain) and D of the blocks' rows, fetched one group of 4 rows ahead
+  f32x4 l4[2][4];                  // lse (log2 domain) of the blocks' rows, fetched one group of 4 rows ahead
   float tq[2][16], uq[2][16];      // per element: exponent then P, and dP - D then dS
   auto vec_group = [&](int qb, int grp) __attribute__((always_inline)) {
     const int row = qb * 32 + 8 * grp + 4 * g;
     l4[qb][grp] = *(const f32x4*)(vec_s + dkdv_vec_off(row, false));
-    d4[qb][grp] = *(const f32x4*)(vec_s + dkdv_vec_off(row, true));
   };
   const char* q_src = nullptr;
   const char* do_src = nullptr;
@@ -420,11 +436,19 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
   for (int x = 0; x < NX; ++x) {
     // --- the MFMA of this step
     if (x < 2 * NST) {
-      const int qb = x / NST, kk = (x % NST) / 2;   // S and dP alternate: two independent accumulation chains
-      if ((x & 1) == 0)
+      const int qb = x / NST, y = x % NST, kk = dkdv_kk<D>(y);   // two independent accumulation chains
+      if (y == 0) {   // the dP accumulator starts from -D of the block's rows (register r: row 8*(r/4) + 4*g + r%4)
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+          const f32x4 dn = *(const f32x4*)(vec_s + dkdv_vec_off(qb * 32 + 8 * grp + 4 * g, true));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pb[qb][4 * grp + i] = dn[i];
+        }
+      }
+      if (dkdv_is_s<D>(y))
         sb[qb] = mfma32(op[x % RD], kreg[kk], kk == 0 ? zero : sb[qb]);
       else
-        pb[qb] = mfma32(op[x % RD], vreg[kk], kk == 0 ? zero : pb[qb]);
+        pb[qb] = mfma32(op[x % RD], vreg[kk], pb[qb]);
     } else {
       const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
       if (u & 1)
@@ -470,7 +494,7 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
         if (stage == 0) {
           if (e0 % 4 == 0 && e0 / 4 + 1 < 4) vec_group(qb, e0 / 4 + 1);
           if (qb == 0 && e0 + EPS == 16) vec_group(1, 0);
-          dkdv_stage_a<MASKED>(sb[qb], pb[qb], tq[qb], uq[qb], l4[qb], d4[qb], e0, EPS, r0 + 32 * qb + 4 * g, sc,
+          dkdv_stage_a<MASKED>(sb[qb], pb[qb], tq[qb], uq[qb], l4[qb], e0, EPS, r0 + 32 * qb + 4 * g, sc,
                        b_lts, b_lte, b_uts, b_ute);
         } else if (stage == 1) {
 #pragma unroll

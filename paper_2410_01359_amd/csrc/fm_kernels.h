@@ -46,7 +46,7 @@ struct FmBwdArgs {
   const int* order_dq;
   const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
   const int* order_dkdv;
-  float* dvec;             // D = rowsum(dO o O), [B,H,N]
+  float* dvec;             // -D = -rowsum(dO o O), [B,H,N] (stored negated)
   float* lse2;             // lse * log2(e), +inf where lse = -inf, [B,H,N]
   void *dq, *dk, *dv;
   float scale;
