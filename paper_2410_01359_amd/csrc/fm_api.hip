@@ -36,7 +36,7 @@ int check_shape(int B, int H, int N, int d) {
 
 // Workspace layout of a pass: tables, work counts and launch order.
 struct PassSpace {
-  size_t minmax, work, order, total;
+  size_t minmax, work, range, order, total;
 };
 PassSpace pass_space(int B, int H, int N, int block_r, int block_c, bool row_units, size_t start) {
   PassSpace s;
@@ -44,7 +44,8 @@ PassSpace pass_space(int B, int H, int N, int block_r, int block_c, bool row_uni
   const size_t per = row_units ? t_r : t_c;
   s.minmax = start;
   s.work = align_up(s.minmax + (size_t)B * 8 * t_c * 4, 256);
-  s.order = align_up(s.work + (size_t)B * per * 4, 256);
+  s.range = align_up(s.work + (size_t)B * per * 4, 256);
+  s.order = align_up(s.range + (size_t)B * per * 8, 256);
   s.total = align_up(s.order + (size_t)fm_order_slots((int)((size_t)B * H * per)) * 4, 256);
   return s;
 }
@@ -130,17 +131,18 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   const PassSpace sp = pass_space(B, H, N, FM_FWD_BR, FM_FWD_BC, true, 0);
   int* minmax = (int*)(ws + sp.minmax);
   int* work = (int*)(ws + sp.work);
+  int* range = (int*)(ws + sp.range);
   int* order = (int*)(ws + sp.order);
   mark(0, stream);
   hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_FWD_BC, minmax, stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_row_order(minmax, B, H, N, FM_FWD_BR, FM_FWD_BC, work, order, stream);
+  e = fm_launch_row_order(minmax, B, H, N, FM_FWD_BR, FM_FWD_BC, work, range, order, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
   FmFwdArgs a;
   a.q = q; a.k = k; a.v = v;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
-  a.minmax = minmax; a.order = order;
+  a.minmax = minmax; a.order = order; a.range = range;
   a.out = out; a.lse = lse; a.scale = scale;
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.slots = fm_order_slots(B * H * (N / FM_FWD_BR));
@@ -170,8 +172,9 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   FmBwdArgs a;
   a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
-  a.minmax_dq = (int*)(ws + sq.minmax); a.order_dq = (int*)(ws + sq.order);
+  a.minmax_dq = (int*)(ws + sq.minmax); a.order_dq = (int*)(ws + sq.order); a.range_dq = (int*)(ws + sq.range);
   a.minmax_dkdv = (int*)(ws + skv.minmax); a.order_dkdv = (int*)(ws + skv.order);
+  a.range_dkdv = (int*)(ws + skv.range);
   a.dvec = (float*)(ws + skv.total);
   a.lse2 = (float*)(ws + skv.total + align_up((size_t)B * H * N * 4, 256));
   a.dq = dq; a.dk = dk; a.dv = dv; a.scale = scale;
@@ -181,12 +184,13 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   mark(0, stream);
   hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_row_order(a.minmax_dq, B, H, N, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.order), stream);
+  e = fm_launch_row_order(a.minmax_dq, B, H, N, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.range),
+                          (int*)(ws + sq.order), stream);
   if (e != hipSuccess) return hip_fail(e);
   e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DKDV_BC, (int*)(ws + skv.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
   e = fm_launch_col_order(a.minmax_dkdv, B, H, N, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
-                          (int*)(ws + skv.order), stream);
+                          (int*)(ws + skv.range), (int*)(ws + skv.order), stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
   e = fm_launch_dvec(a, stream);

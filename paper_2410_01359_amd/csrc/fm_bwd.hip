@@ -142,8 +142,10 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
   }
 
-  for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
-    const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N),
+  // only the key blocks [j_lo, j_hi) can be live for this row block (found by the work pre-pass)
+  const int j_lo = a.range_dq[2 * ((size_t)b * t_r + i_blk)], j_hi = a.range_dq[2 * ((size_t)b * t_r + i_blk) + 1];
+  for (int chunk = j_lo; chunk < j_hi; chunk += C::LIST_CAP) {
+    const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, j_hi), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
     const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
@@ -618,9 +620,11 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     e_cur = __builtin_amdgcn_readfirstlane(v_next);                                                    \
   }
 
-  for (int chunk = 0; chunk < t_r; chunk += C::LIST_CAP) {
+  // only the row blocks [i_lo, i_hi) can be live for this key block (found by the work pre-pass)
+  const int i_lo = a.range_dkdv[2 * ((size_t)b * t_c + j_blk)], i_hi = a.range_dkdv[2 * ((size_t)b * t_c + j_blk) + 1];
+  for (int chunk = i_lo; chunk < i_hi; chunk += C::LIST_CAP) {
     int n_plain = 0;
-    const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, t_r), list, wave_cnt, n_plain);
+    const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, i_hi), list, wave_cnt, n_plain);
     if (n_live == 0) continue;
     // prologue: copies of the first NSTAGE - 1 tiles, then the first tile's first operands
 #pragma unroll

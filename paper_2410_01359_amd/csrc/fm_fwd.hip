@@ -253,8 +253,10 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
     barrier_nofence(); /* ... for every wave, and every wave is done with K(T+1) and V(T) */     \
   }
 
-  for (int chunk = 0; chunk < t_c; chunk += C::LIST_CAP) {
-    const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, t_c), q0, min(q0 + C::BR, N),
+  // only the key blocks [j_lo, j_hi) can be live for this row block (found by the work pre-pass)
+  const int j_lo = a.range[2 * ((size_t)b * t_r + i_blk)], j_hi = a.range[2 * ((size_t)b * t_r + i_blk) + 1];
+  for (int chunk = j_lo; chunk < j_hi; chunk += C::LIST_CAP) {
+    const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, j_hi), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
     {

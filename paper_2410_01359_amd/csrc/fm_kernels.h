@@ -19,17 +19,19 @@ hipError_t fm_launch_preprocess(const int* lts, const int* lte, const int* uts, 
                                 int block_c, int* minmax, hipStream_t stream);
 hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int block_c, uint8_t* cls,
                               hipStream_t stream);
-// work: int[B * T_r] (resp. B * T_c); order: int[fm_order_slots(B*H*T)].
+// work: int[B * T_r] (resp. B * T_c); range: int[2 * B * T] = first live block and one past the
+// last live block of every unit (0, 0 if none); order: int[fm_order_slots(B*H*T)].
 hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
-                               int* order, hipStream_t stream);
+                               int* range, int* order, hipStream_t stream);
 hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
-                               int* order, hipStream_t stream);
+                               int* range, int* order, hipStream_t stream);
 
 struct FmFwdArgs {
   const void *q, *k, *v;
   const int *lts, *lte, *uts, *ute;
   const int* minmax;  // [B][8][T_c] at FM_FWD_BC
   const int* order;   // launch slots -> unit (b*H + h)*T_r + i, or -1
+  const int* range;   // [B][T_r][2]: key blocks [first, last) outside of which the row block is fully masked
   void* out;
   float* lse;
   float scale;
@@ -44,8 +46,10 @@ struct FmBwdArgs {
   const int *lts, *lte, *uts, *ute;
   const int* minmax_dq;    // [B][8][T_c] at FM_DQ_BC
   const int* order_dq;
+  const int* range_dq;     // [B][T_r][2] key-block range of each row block
   const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
   const int* order_dkdv;
+  const int* range_dkdv;   // [B][T_c][2] row-block range of each key block
   float* dvec;             // -D = -rowsum(dO o O), [B,H,N] (stored negated)
   float* lse2;             // lse * log2(e), +inf where lse = -inf, [B,H,N]
   void *dq, *dk, *dv;

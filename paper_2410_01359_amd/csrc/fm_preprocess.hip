@@ -62,39 +62,67 @@ __global__ __launch_bounds__(256) void classify_kernel(const int* __restrict__ m
   cls[((size_t)b * t_r + i) * t_c + j] = (uint8_t)classify_tile(r0, r1, t);
 }
 
-// Work of one row block = number of key blocks that are not fully masked.
+// Work of one row block = number of key blocks that are not fully masked, and
+// the range of key blocks that contains them (the tile loops only scan that).
 // One wave per (batch row, row block); lanes stride over the key blocks.
 __global__ __launch_bounds__(256) void row_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
-                                                       int t_c, int total_units, int* __restrict__ work) {
+                                                       int t_c, int total_units, int* __restrict__ work,
+                                                       int* __restrict__ range) {
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (u >= total_units) return;
   const int b = u / t_r, i = u - b * t_r;
   const int r0 = i * block_r, r1 = min(r0 + block_r, n);
   const int* table = minmax + (size_t)b * 8 * t_c;
-  int cnt = 0;
-  for (int j = lane; j < t_c; j += 64) cnt += (classify_tile(r0, r1, load_minmax(table, t_c, j)) != T_FULLY);
+  int cnt = 0, lo = t_c, hi = 0;
+  for (int j = lane; j < t_c; j += 64)
+    if (classify_tile(r0, r1, load_minmax(table, t_c, j)) != T_FULLY) {
+      ++cnt;
+      lo = min(lo, j);
+      hi = j + 1;
+    }
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
-  if (lane == 0) work[u] = cnt;
+  for (int off = 32; off >= 1; off >>= 1) {
+    cnt += __shfl_xor(cnt, off, 64);
+    lo = min(lo, __shfl_xor(lo, off, 64));
+    hi = max(hi, __shfl_xor(hi, off, 64));
+  }
+  if (lane == 0) {
+    work[u] = cnt;
+    range[2 * u] = cnt ? lo : 0;
+    range[2 * u + 1] = hi;
+  }
 }
 
 // Work of one key block = number of row blocks that are not fully masked.
 __global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
-                                                       int t_c, int total_units, int* __restrict__ work) {
+                                                       int t_c, int total_units, int* __restrict__ work,
+                                                       int* __restrict__ range) {
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (u >= total_units) return;
   const int b = u / t_c, j = u - b * t_c;
   const MinMax8 t = load_minmax(minmax + (size_t)b * 8 * t_c, t_c, j);
-  int cnt = 0;
+  int cnt = 0, lo = t_r, hi = 0;
   for (int i = lane; i < t_r; i += 64) {
     const int r0 = i * block_r, r1 = min(r0 + block_r, n);
-    cnt += (classify_tile(r0, r1, t) != T_FULLY);
+    if (classify_tile(r0, r1, t) != T_FULLY) {
+      ++cnt;
+      lo = min(lo, i);
+      hi = i + 1;
+    }
   }
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
-  if (lane == 0) work[u] = cnt;
+  for (int off = 32; off >= 1; off >>= 1) {
+    cnt += __shfl_xor(cnt, off, 64);
+    lo = min(lo, __shfl_xor(lo, off, 64));
+    hi = max(hi, __shfl_xor(hi, off, 64));
+  }
+  if (lane == 0) {
+    work[u] = cnt;
+    range[2 * u] = cnt ? lo : 0;
+    range[2 * u + 1] = hi;
+  }
 }
 
 // Launch order (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8
@@ -188,24 +216,24 @@ hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int 
 }
 
 hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
-                               int* order, hipStream_t stream) {
+                               int* range, int* order, hipStream_t stream) {
   const int t_c = (N + block_c - 1) / block_c;
   const int t_r = (N + block_r - 1) / block_r;
   const int total = B * t_r;
   hipLaunchKernelGGL(row_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
-                     work);
+                     work, range);
   hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, B, H, t_r, t_c,
                      fm_order_slots(B * H * t_r), order);
   return hipGetLastError();
 }
 
 hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
-                               int* order, hipStream_t stream) {
+                               int* range, int* order, hipStream_t stream) {
   const int t_c = (N + block_c - 1) / block_c;
   const int t_r = (N + block_r - 1) / block_r;
   const int total = B * t_c;
   hipLaunchKernelGGL(col_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
-                     work);
+                     work, range);
   hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, B, H, t_c, t_r,
                      fm_order_slots(B * H * t_c), order);
   return hipGetLastError();
