@@ -6,7 +6,7 @@ One "step" = one forward + one backward pass of the whole C-ABI path
 synthetic bf16 input already resident in HBM.  Throughput counts only unmasked
 FLOPs: 4*d per unmasked score element forward, 2.5x that backward.
 
-Prints ONE JSON line ("Measurement").
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -163,7 +163,7 @@ def main():
                          "HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (batch x heads is the sharding axis; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU only (batch x heads is the sharding axis); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
