@@ -174,15 +174,37 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
             sacc[r] = 0.f;
             dpacc[r] = 0.f;
           }
-          // S^T = K Q^T and dP^T = V dO^T for 32 keys x 32 queries
+          // S^T = K Q^T and dP^T = V dO^T for 32 keys x 32 queries: 2*NKK MFMA steps, S and dP
+          // alternating (two accumulation chains); the LDS operand of a step is fetched RS steps
+          // ahead into a small register ring.
+          constexpr int NS = 2 * NKK, RS = 4, NT = 2 * NDB, RT = 3;
+          auto s_operand = [&](int n) __attribute__((always_inline)) {
+            const char* tile = (n & 1) ? vs : ks;
+            return *(const bf16x8*)(tile + kb * 32 * C::L::RS + C::L::add_col(a_b, (n / 2) * 32));
+          };
+          auto t_operand = [&](int n) __attribute__((always_inline)) {
+            const char* krow = ks + (kb * 32 + 16 * (n / NDB)) * C::L::RS;
+            return cat4(lds_read_tr16(krow + C::L::add_col(t_b0, (n % NDB) * 64)),
+                        lds_read_tr16(krow + C::L::add_col(t_b1, (n % NDB) * 64)));
+          };
+          bf16x8 ring[RS];
 #pragma unroll
-          for (int kk = 0; kk < NKK; ++kk) {
-            const int ao = C::L::add_col(a_b, kk * 32);
-            const bf16x8 ka = *(const bf16x8*)(ks + kb * 32 * C::L::RS + ao);
-            sacc = mfma32(ka, qreg[kk], sacc);
-            const bf16x8 va = *(const bf16x8*)(vs + kb * 32 * C::L::RS + ao);
-            dpacc = mfma32(va, doreg[kk], dpacc);
+          for (int n = 0; n < RS; ++n) ring[n] = s_operand(n);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int n = 0; n < NS; ++n) {
+            if (n & 1)
+              dpacc = mfma32(ring[n % RS], doreg[n / 2], dpacc);
+            else
+              sacc = mfma32(ring[n % RS], qreg[n / 2], sacc);
+            if (n + RS < NS) ring[n % RS] = s_operand(n + RS);
+            __builtin_amdgcn_sched_barrier(0);
           }
+          // K^T operands of the dQ product do not depend on dS: fetch the first ones now
+          bf16x8 tring[RT];
+#pragma unroll
+          for (int n = 0; n < RT; ++n) tring[n] = t_operand(n);
+          __builtin_amdgcn_sched_barrier(0);
           if (wcls & T_PARTIAL) {
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
@@ -205,21 +227,18 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
             sacc[r] = p * (dpacc[r] + dneg);
           }
           __builtin_amdgcn_sched_barrier(0);
-          // dQ^T += K^T dS^T
+          // dQ^T += K^T dS^T, step n = (16-key half n / NDB, d block n % NDB)
+          bf16x8 dsb;
 #pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            bf16x8 dsb;
+          for (int n = 0; n < NT; ++n) {
+            if (n % NDB == 0) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dsb[e] = (__bf16)sacc[8 * h + e];
-            const char* krow = ks + (kb * 32 + 16 * h) * C::L::RS;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-              const bf16x4 lo = lds_read_tr16(krow + C::L::add_col(t_b0, db * 64));
-              const bf16x4 hi = lds_read_tr16(krow + C::L::add_col(t_b1, db * 64));
-              dqacc[db] = mfma32(cat4(lo, hi), dsb, dqacc[db]);
+              for (int e = 0; e < 8; ++e) dsb[e] = (__bf16)sacc[8 * (n / NDB) + e];
             }
+            dqacc[n % NDB] = mfma32(tring[n % RT], dsb, dqacc[n % NDB]);
+            if (n + RT < NT) tring[n % RT] = t_operand(n + RT);
+            __builtin_amdgcn_sched_barrier(0);
           }
-          __builtin_amdgcn_sched_barrier(0);
         }
       }
 
