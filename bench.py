@@ -67,7 +67,8 @@ def device_inputs(w, torch):
 
 
 def run_workload(name, steps, warmup, torch, fm, orc, workloads, hip, with_events):
-    w = workloads.config(name)
+    w = name if isinstance(name, workloads.Workload) else workloads.config(name)
+    name = w.name
     t, vecs = device_inputs(w, torch)
     ws = torch.empty(max(fm.flashmask_workspace_bytes(fm.FM_PASS_BWD, w.B, w.H, w.N, w.d),
                          fm.flashmask_workspace_bytes(fm.FM_PASS_FWD, w.B, w.H, w.N, w.d)),
@@ -149,6 +150,26 @@ def cpu_baseline(w, orc, workloads, budget_rows):
                       f"workload {w.name} ({secs:.1f} s; dense work, unmasked FLOPs counted)"}
 
 
+def sparsity_sweep(torch, fm, orc, workloads, hip, steps, warmup):
+    """Wall time of forward+backward against the fraction of tiles that are not skipped, at the
+    shape of config 4 with causal-document masks (equal and random partitions); least-squares line."""
+    pts = []
+    for w in workloads.sweep_workloads():
+        r = run_workload(w, steps, warmup, torch, fm, orc, workloads, hip, False)
+        pts.append({"workload": w.name, "docs": len(w.structure[0]), "block_sparsity": round(r["block_sparsity"], 4),
+                    "ms": round(r["ms_per_step"], 4), "tflops": round(r["tflops"], 1)})
+        torch.cuda.empty_cache()
+    x = np.array([1.0 - p["block_sparsity"] for p in pts])
+    y = np.array([p["ms"] for p in pts])
+    slope, intercept = np.polyfit(x, y, 1)
+    resid = y - (slope * x + intercept)
+    r2 = 1.0 - float(resid @ resid) / float(((y - y.mean()) @ (y - y.mean())))
+    return {"metric": "fwd+bwd ms vs fraction of 128x128 tiles not skipped (1 - block sparsity)",
+            "shape": "B=1, H=16, N=32768, d=128, causal-document masks", "steps": steps, "warmup": warmup,
+            "fit": {"slope_ms": round(float(slope), 4), "intercept_ms": round(float(intercept), 4), "r2": round(r2, 5)},
+            "points": pts}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,6 +179,8 @@ def main():
     ap.add_argument("--others", default="2,3,4a,4b", help="extra workloads reported in `other_workloads` ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line, print the block-sparsity sweep (time vs 1 - sparsity)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (read once, written once): a kernel of known "
                          "HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -177,6 +200,10 @@ def main():
         sys.exit(2)
     fm.load_library()
     hip = hip_runtime()
+
+    if args.sweep:
+        print(json.dumps(sparsity_sweep(torch, fm, orc, workloads, hip, max(3, args.steps // 4), 2)), flush=True)
+        return
 
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, fm, orc, workloads, hip, True)
     w = main_res.pop("workload_obj")

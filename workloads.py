@@ -292,6 +292,29 @@ def config(name: str) -> Workload:
 CONFIG_NAMES = ("1", "2", "3", "4a", "4b", "5")
 
 
+def sweep_workloads(n_random: int = 20):
+    """Workloads of the block-sparsity sweep: the shape of config 4 (B=1, H=16, N=32768, d=128)
+    with causal-document masks of 1, 2, 4, ..., 128 equal documents and `n_random` seeded random
+    partitions (2..64 documents, uniform composition with floor 128)."""
+    out = []
+    N = 32768
+    for k, n_docs in enumerate((1, 2, 4, 8, 16, 32, 64, 128)):
+        w = Workload(f"sweep-eq{n_docs}", 1, 16, N, 128, BASE_SEED + 600 + k, "causal_document")
+        spans = spans_from_lengths([N // n_docs] * n_docs)
+        w.structure = [spans]
+        w.vectors = [causal_document_mask(N, spans)]
+        out.append(w)
+    for k in range(n_random):
+        w = Workload(f"sweep-rand{k}", 1, 16, N, 128, BASE_SEED + 650 + k, "causal_document")
+        rng = _mask_rng(w.seed)
+        n_docs = int(rng.integers(2, 65))
+        spans = spans_from_lengths(sample_partition(rng, N, n_docs, 128))
+        w.structure = [spans]
+        w.vectors = [causal_document_mask(N, spans)]
+        out.append(w)
+    return out
+
+
 def small_workload(mask_kind: str, N: int, seed: int, B: int = 1, H: int = 1, d: int = 64) -> Workload:
     """Small seeded case of any mask family, for parity tests."""
     w = Workload(f"small-{mask_kind}-{N}", B, H, N, d, seed, mask_kind)
