@@ -564,26 +564,22 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const float* lsep = a.lse2 + (size_t)bh * N;
   const float* dvp = a.dvec + (size_t)bh * N;
 
-  // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T)
+  // What the list of live row blocks needs comes first, so that its latency is not queued
+  // behind the fragment loads below: the block's min/max values and its live row-block range.
+  const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
+  const int i_lo = a.range_dkdv[2 * ((size_t)b * t_c + j_blk)], i_hi = a.range_dkdv[2 * ((size_t)b * t_c + j_blk) + 1];
+
+  // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T) and the four
+  // bounds of this lane's key, which stay in registers (Algorithm 2 loads them once per key
+  // block).  They are only waited for after the first tile copies have been issued.
   bf16x8 kreg[NKK], vreg[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
     kreg[kk] = *(const bf16x8*)(kp + (size_t)key * D + kk * 16 + 8 * g);
     vreg[kk] = *(const bf16x8*)(vp + (size_t)key * D + kk * 16 + 8 * g);
   }
-  // the four bounds of this lane's key stay in registers (Algorithm 2 loads them once per key block)
   int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
   int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
-#pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) {
-    settle(kreg[kk]);
-    settle(vreg[kk]);
-  }
-  settle(b_lts);
-  settle(b_lte);
-  settle(b_uts);
-  settle(b_ute);
-  const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
 
   f32x16 dkacc[NDB], dvacc[NDB];
 #pragma unroll
@@ -640,7 +636,6 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   }
 
   // only the row blocks [i_lo, i_hi) can be live for this key block (found by the work pre-pass)
-  const int i_lo = a.range_dkdv[2 * ((size_t)b * t_c + j_blk)], i_hi = a.range_dkdv[2 * ((size_t)b * t_c + j_blk) + 1];
   for (int chunk = i_lo; chunk < i_hi; chunk += C::LIST_CAP) {
     int n_plain = 0;
     const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, i_hi), list, wave_cnt, n_plain);
@@ -654,6 +649,18 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
       tile_load_async<D>(dop + (size_t)i_p * QT * D, copy_lanes, st_ + C::Q_BYTES, wave);
       async_copy16_lanes8(my_vec + i_p * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES) + wave * 128);
     }
+    // The fragment and bound loads must be complete, and known complete to the compiler, before
+    // the tile loops: a compiler-inserted wait for them inside a loop would also drain the
+    // copies in flight there.  (No-op after the first chunk.)
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      settle(kreg[kk]);
+      settle(vreg[kk]);
+    }
+    settle(b_lts);
+    settle(b_lte);
+    settle(b_uts);
+    settle(b_ute);
     async_wait<(C::NSTAGE - 2) * C::NC>();
     barrier_nofence();
     int e_cur = __builtin_amdgcn_readfirstlane(list[0]);
