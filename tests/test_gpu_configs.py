@@ -104,3 +104,44 @@ def test_config_zero_query_closed_form_every_head(name):
     ro, _ = orc.forward_rows(np.zeros_like(v0), v0, v0, *w.vectors[0], w.scale, rows)
     got = bf16_to_np(out[0, 0][rows])
     assert np.abs(got - ro).max() <= ABS_FWD
+
+
+OTHER_FAMILIES = ["document", "prefix_document", "global_sliding_window", "causal_blockwise", "random_eviction",
+                  "random_intervals"]
+
+
+@pytest.mark.parametrize("kind", OTHER_FAMILIES)
+def test_other_mask_families_at_16k(kind):
+    """The mask families outside the five configurations (both interval pairs active, union
+    covers, mostly-partial tiles), at N = 16384, d = 128, on sampled rows and columns."""
+    import paper_2410_01359_amd as fm
+    w = workloads.small_workload(kind, 16384, seed=4100 + len(kind), B=1, H=2, d=128)
+    bits, dev, vecs = to_device(w)
+    out, lse = fm.flashmask_fwd(dev["q"], dev["k"], dev["v"], *vecs, w.scale)
+    dq, dk, dv = fm.flashmask_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], *vecs, w.scale)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(w.seed)
+    vec = w.vectors[0]
+    rows = sample_rows(w, vec, rng, n_random=64)
+    cols = sample_cols(w, vec, rng, row_budget=8192)
+    for h in range(w.H):
+        args = [f64(bits[n][0, h]) for n in ("q", "k", "v", "dout")]
+        what = f"{kind} N=16384 h={h}"
+        ro, rl = orc.forward_rows(args[0], args[1], args[2], *vec, w.scale, rows)
+        check_fwd(bf16_to_np(out[0, h][rows]), lse[0, h][rows].cpu().numpy(), ro, rl, what)
+        rdq = orc.backward_rows(*args, *vec, w.scale, rows)
+        check_bwd(bf16_to_np(dq[0, h][rows]), rdq, "dq", what)
+        if len(cols):
+            rdk, rdv = orc.backward_cols(*args, *vec, w.scale, cols)
+            check_bwd(bf16_to_np(dk[0, h][cols]), rdk, "dk", what)
+            check_bwd(bf16_to_np(dv[0, h][cols]), rdv, "dv", what)
+    # every head: with Q = 0, lse = log(number of visible keys), -inf where a row sees nothing
+    out0, lse0 = fm.flashmask_fwd(torch.zeros_like(dev["q"]), dev["v"], dev["v"], *vecs, w.scale)
+    torch.cuda.synchronize()
+    c = orc.allowed_keys_per_row(*vec).astype(np.float64)
+    with np.errstate(divide="ignore"):
+        want = np.log(c)
+    got = lse0[0].cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isneginf(got), np.isneginf(want)[None, :].repeat(w.H, 0))
+    fin = np.isfinite(want)
+    assert np.abs(got[:, fin] - want[fin][None, :]).max() <= ABS_FWD
