@@ -20,8 +20,9 @@
  *   - lts, lte, uts, ute: int32, contiguous [B, N]; one mask per batch row,
  *     shared by all heads.
  *   - lse, and the library's own D vector: fp32 [B, H, N].
- *   - d must be 64 or 128; N must be a positive multiple of 128; tensor
- *     pointers must be 16-byte aligned.
+ *   - d must be 64 or 128; N is any positive length (a length that is not a
+ *     multiple of 128 costs one small extra launch that pads the bound
+ *     vectors inside the workspace); tensor pointers must be 16-byte aligned.
  *   - Outputs are overwritten in full.
  *   - Return value: FM_OK (0) or a negative FM_ERR_* code.  Only conditions the
  *     host can see are checked; bound VALUES live on the device and are not
@@ -41,7 +42,7 @@ extern "C" {
 enum {
   FM_OK = 0,
   FM_ERR_NULL = -1,      /* a required pointer is NULL */
-  FM_ERR_SHAPE = -2,     /* B, H, N <= 0, d not in {64,128}, N not a multiple of 128, bad block size */
+  FM_ERR_SHAPE = -2,     /* B, H, N <= 0, d not in {64,128}, sizes beyond 32-bit indexing, bad block size */
   FM_ERR_ALIGN = -3,     /* a tensor pointer is not 16-byte aligned */
   FM_ERR_WORKSPACE = -4, /* workspace is NULL or smaller than flashmask_workspace_bytes() */
   FM_ERR_HIP = -5,       /* a kernel launch failed; see flashmask_last_hip_error() */

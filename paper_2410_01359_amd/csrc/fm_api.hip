@@ -29,9 +29,16 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 int check_shape(int B, int H, int N, int d) {
   if (B <= 0 || H <= 0 || N <= 0) return FM_ERR_SHAPE;
   if (d != 64 && d != 128) return FM_ERR_SHAPE;
-  if (N % 128 != 0) return FM_ERR_SHAPE;
-  if ((long long)B * H * (N / 64) >= (1ll << 31) / 8) return FM_ERR_SHAPE;
+  if (N > (1 << 30)) return FM_ERR_SHAPE;
+  if ((long long)B * H * ((N + 127) / 128 * 2) >= (1ll << 31) / 8) return FM_ERR_SHAPE;
   return FM_OK;
+}
+
+// The tile loops work at the sequence length rounded up to a multiple of 128; a sequence that is
+// not such a multiple gets padded copies of its bound vectors at the front of the workspace.
+inline int padded_len(int N) { return (N + 127) / 128 * 128; }
+inline size_t padded_bounds_bytes(int B, int N) {
+  return padded_len(N) == N ? 0 : align_up((size_t)4 * B * padded_len(N) * 4, 256);
 }
 
 // Workspace layout of a pass: tables, work counts and launch order.
@@ -58,7 +65,7 @@ const char* flashmask_strerror(int code) {
   switch (code) {
     case FM_OK: return "ok";
     case FM_ERR_NULL: return "a required pointer is NULL";
-    case FM_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, d in {64,128}, N a multiple of 128)";
+    case FM_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, d in {64,128})";
     case FM_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
     case FM_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
     case FM_ERR_HIP: return "HIP launch failed (see flashmask_last_hip_error)";
@@ -89,11 +96,13 @@ int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c) {
 
 size_t flashmask_workspace_bytes(int pass, int B, int H, int N, int d) {
   if (check_shape(B, H, N, d) != FM_OK) return 0;
-  if (pass == FM_PASS_FWD) return pass_space(B, H, N, FM_FWD_BR, FM_FWD_BC, true, 0).total;
+  const int Np = padded_len(N);
+  const size_t pad = padded_bounds_bytes(B, N);
+  if (pass == FM_PASS_FWD) return pad + pass_space(B, H, Np, FM_FWD_BR, FM_FWD_BC, true, 0).total;
   if (pass == FM_PASS_BWD) {
-    const PassSpace dq = pass_space(B, H, N, FM_DQ_BR, FM_DQ_BC, true, 0);
-    const PassSpace kv = pass_space(B, H, N, FM_DKDV_BR, FM_DKDV_BC, false, dq.total);
-    return kv.total + 2 * align_up((size_t)B * H * N * 4, 256);  // + D vector + log2-domain lse
+    const PassSpace dq = pass_space(B, H, Np, FM_DQ_BR, FM_DQ_BC, true, 0);
+    const PassSpace kv = pass_space(B, H, Np, FM_DKDV_BR, FM_DKDV_BC, false, dq.total);
+    return pad + kv.total + 2 * align_up((size_t)B * H * Np * 4, 256);  // + D vector + log2-domain lse
   }
   return 0;
 }
@@ -127,16 +136,26 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   const size_t need = flashmask_workspace_bytes(FM_PASS_FWD, B, H, N, d);
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FM_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)hip_stream;
+  const int Np = padded_len(N);
   char* ws = (char*)workspace;
-  const PassSpace sp = pass_space(B, H, N, FM_FWD_BR, FM_FWD_BC, true, 0);
+  mark(0, stream);
+  hipError_t e;
+  if (Np != N) {   // padded bound vectors first
+    int* padded = (int*)ws;
+    e = fm_launch_pad_bounds(lts, lte, uts, ute, B, N, Np, padded, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    const size_t plane = (size_t)B * Np;
+    lts = padded; lte = padded + plane; uts = padded + 2 * plane; ute = padded + 3 * plane;
+    ws += padded_bounds_bytes(B, N);
+  }
+  const PassSpace sp = pass_space(B, H, Np, FM_FWD_BR, FM_FWD_BC, true, 0);
   int* minmax = (int*)(ws + sp.minmax);
   int* work = (int*)(ws + sp.work);
   int* range = (int*)(ws + sp.range);
   int* order = (int*)(ws + sp.order);
-  mark(0, stream);
-  hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_FWD_BC, minmax, stream);
+  e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_FWD_BC, minmax, stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_row_order(minmax, B, H, N, FM_FWD_BR, FM_FWD_BC, work, range, order, stream);
+  e = fm_launch_row_order(minmax, B, H, Np, FM_FWD_BR, FM_FWD_BC, work, range, order, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
   FmFwdArgs a;
@@ -144,8 +163,8 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
   a.minmax = minmax; a.order = order; a.range = range;
   a.out = out; a.lse = lse; a.scale = scale;
-  a.B = B; a.H = H; a.N = N; a.d = d;
-  a.slots = fm_order_slots(B * H * (N / FM_FWD_BR));
+  a.B = B; a.H = H; a.N = N; a.Np = Np; a.d = d;
+  a.slots = fm_order_slots(B * H * (Np / FM_FWD_BR));
   e = fm_launch_fwd(a, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(2, stream);
@@ -166,9 +185,20 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   const size_t need = flashmask_workspace_bytes(FM_PASS_BWD, B, H, N, d);
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FM_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)hip_stream;
+  const int Np = padded_len(N);
   char* ws = (char*)workspace;
-  const PassSpace sq = pass_space(B, H, N, FM_DQ_BR, FM_DQ_BC, true, 0);
-  const PassSpace skv = pass_space(B, H, N, FM_DKDV_BR, FM_DKDV_BC, false, sq.total);
+  mark(0, stream);
+  hipError_t e;
+  if (Np != N) {   // padded bound vectors first
+    int* padded = (int*)ws;
+    e = fm_launch_pad_bounds(lts, lte, uts, ute, B, N, Np, padded, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    const size_t plane = (size_t)B * Np;
+    lts = padded; lte = padded + plane; uts = padded + 2 * plane; ute = padded + 3 * plane;
+    ws += padded_bounds_bytes(B, N);
+  }
+  const PassSpace sq = pass_space(B, H, Np, FM_DQ_BR, FM_DQ_BC, true, 0);
+  const PassSpace skv = pass_space(B, H, Np, FM_DKDV_BR, FM_DKDV_BC, false, sq.total);
   FmBwdArgs a;
   a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
@@ -176,20 +206,19 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   a.minmax_dkdv = (int*)(ws + skv.minmax); a.order_dkdv = (int*)(ws + skv.order);
   a.range_dkdv = (int*)(ws + skv.range);
   a.dvec = (float*)(ws + skv.total);
-  a.lse2 = (float*)(ws + skv.total + align_up((size_t)B * H * N * 4, 256));
+  a.lse2 = (float*)(ws + skv.total + align_up((size_t)B * H * Np * 4, 256));
   a.dq = dq; a.dk = dk; a.dv = dv; a.scale = scale;
-  a.B = B; a.H = H; a.N = N; a.d = d;
-  a.slots_dq = fm_order_slots(B * H * (N / FM_DQ_BR));
-  a.slots_dkdv = fm_order_slots(B * H * (N / FM_DKDV_BC));
-  mark(0, stream);
-  hipError_t e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
+  a.B = B; a.H = H; a.N = N; a.Np = Np; a.d = d;
+  a.slots_dq = fm_order_slots(B * H * (Np / FM_DQ_BR));
+  a.slots_dkdv = fm_order_slots(B * H * (Np / FM_DKDV_BC));
+  e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_row_order(a.minmax_dq, B, H, N, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.range),
+  e = fm_launch_row_order(a.minmax_dq, B, H, Np, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.range),
                           (int*)(ws + sq.order), stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_preprocess(lts, lte, uts, ute, B, N, FM_DKDV_BC, (int*)(ws + skv.minmax), stream);
+  e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_DKDV_BC, (int*)(ws + skv.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_col_order(a.minmax_dkdv, B, H, N, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
+  e = fm_launch_col_order(a.minmax_dkdv, B, H, Np, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
                           (int*)(ws + skv.range), (int*)(ws + skv.order), stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);

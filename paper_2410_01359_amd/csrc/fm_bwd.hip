@@ -23,13 +23,17 @@ namespace fm {
 template <int D>
 __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                                                    const float* __restrict__ lse, float* __restrict__ dvec,
-                                                   float* __restrict__ lse2, long long rows) {
+                                                   float* __restrict__ lse2, long long slices, int n, int np) {
   constexpr int LPR = D / 8;  // lanes per row
   const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long row = gid / LPR;
+  const long long prow = gid / LPR;              // row index in the padded [slices][np] layout
   const int part = (int)(gid % LPR);
+  const long long bh = prow / np;
+  const int r = (int)(prow % np);
+  const bool real = bh < slices && r < n;        // rows r >= n are the padding of a ragged sequence
+  const long long row = bh * n + r;
   float acc = 0.f;
-  if (row < rows) {
+  if (real) {
     const bf16x8 o = *(const bf16x8*)(out + row * D + part * 8);
     const bf16x8 g = *(const bf16x8*)(dout + row * D + part * 8);
 #pragma unroll
@@ -37,12 +41,12 @@ __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ ou
   }
 #pragma unroll
   for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (row < rows && part == 0) {
-    dvec[row] = -acc;   // stored negated: the tile loops add it
-    // lse for the backward's exponent: log2 domain, and +inf for a row with no
-    // visible key (lse = -inf) so that exp2(s - lse2) is exactly 0 there
-    const float l = lse[row];
-    lse2[row] = (l == -INFINITY) ? INFINITY : l * kLog2e;
+  if (bh < slices && part == 0) {
+    dvec[prow] = -acc;   // stored negated: the tile loops add it (0 in the padding)
+    // lse for the backward's exponent: log2 domain, and +inf for a row with no visible key
+    // (lse = -inf) and for padding rows, so that exp2(s - lse2) is exactly 0 there
+    const float l = real ? lse[row] : -INFINITY;
+    lse2[prow] = (l == -INFINITY) ? INFINITY : l * kLog2e;
   }
 }
 
@@ -64,7 +68,8 @@ struct DqCfg {
   static constexpr int LDS_BYTES = STAGE_OFF + 2 * STAGE;
 };
 
-template <int D>
+// RAGGED: see the forward kernel -- loops at the padded length, clamped tile copies, guarded stores.
+template <int D, bool RAGGED>
 __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   using C = DqCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
@@ -75,17 +80,19 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, c = lane & 31;
-  const int N = a.N, H = a.H;
+  const int N = a.Np, H = a.H;            // padded length: what the loops and tables see
+  const int Nr = RAGGED ? a.N : a.Np;     // rows the tensors really have
   const int t_r = N / C::BR, t_c = N / KT;
   const int bh = unit / t_r, i_blk = unit - bh * t_r, b = bh / H;
   const int q0 = i_blk * C::BR;
   const int qw0 = q0 + wave * 32;
   const int row = qw0 + c;  // this lane's query row
+  const int row_ld = RAGGED ? min(row, Nr - 1) : row;
 
-  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * N * D;
-  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * N * D;
-  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * N * D;
-  const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * N * D;
+  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * Nr * D;
+  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * Nr * D;
+  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * Nr * D;
+  const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * Nr * D;
   const int* table = a.minmax_dq + (size_t)b * 8 * t_c;
   // lanes of wave 0 copy the four bound slices of a partially masked tile
   const int* my_bvec;
@@ -103,8 +110,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   bf16x8 qreg[NKK], doreg[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    qreg[kk] = *(const bf16x8*)(qp + (size_t)row * D + kk * 16 + 8 * g);
-    doreg[kk] = *(const bf16x8*)(dop + (size_t)row * D + kk * 16 + 8 * g);
+    qreg[kk] = *(const bf16x8*)(qp + (size_t)row_ld * D + kk * 16 + 8 * g);
+    doreg[kk] = *(const bf16x8*)(dop + (size_t)row_ld * D + kk * 16 + 8 * g);
   }
   // lse in the log2 domain (+inf for a row with no visible key, so that P = 0 there)
   float lse2 = a.lse2[(size_t)bh * N + row];
@@ -136,8 +143,13 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   {                                                                                            \
     const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
-    tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                     \
-    tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_ + C::K_BYTES, wave);        \
+    if (RAGGED && (j_ + 1) * KT > Nr) {                                                        \
+      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane);                            \
+      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_ + C::K_BYTES, wave, lane);               \
+    } else {                                                                                   \
+      tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                     \
+      tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_ + C::K_BYTES, wave);        \
+    }                                                                                          \
     if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
   }
@@ -249,7 +261,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   }
 #undef FM_LOAD_TILE
 
-  __bf16* dqp = (__bf16*)a.dq + (size_t)bh * N * D;
+  __bf16* dqp = (__bf16*)a.dq + (size_t)bh * Nr * D;
+  if (RAGGED && row >= Nr) return;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -346,22 +359,33 @@ struct DkdvAhead {
   const float* vec_src;
   unsigned lds_ring;      // LDS address of stage 0
   unsigned stage_copy;    // index of the stage that receives the copy
+  int n_real, lane;       // ragged sequences: rows the tensors really have, and this thread's lane
   CopyLanes<128> lanes;   // per-lane source offsets of the copy instructions (the first D/32 entries are used)
   int wave;
 };
 
-// Copy number K (of NC) of the tile whose 64-row base offsets are given.
-template <int D, int K>
+// Copy number K (of NC) of the tile whose 64-row base offsets are given.  RAGGED: a tile that
+// reaches past the last real row (i_copy is its index) clamps every lane's source row instead.
+template <int D, int K, bool RAGGED>
 __device__ __forceinline__ void dkdv_issue_copy(const DkdvAhead& ah, const char* q_src, const char* do_src,
-                                                const float* vec_src, unsigned lds_stage) {
+                                                const float* vec_src, unsigned lds_stage, int i_copy) {
   using C = DkdvCfg<D>;
   constexpr int HALF = C::COPIES / 2;
   constexpr int WB = 16 * C::L::RS;   // bytes of a wave's 16-row block
+  if (RAGGED && K < C::COPIES && (i_copy + 1) * C::QT > ah.n_real) {
+    constexpr int RPI = 64 / C::L::CPR, S = K % HALF;
+    const int row = ah.wave * 16 + S * RPI + ah.lane / C::L::CPR;
+    const int grow = min(i_copy * C::QT + row, ah.n_real - 1);
+    const char* base = K < HALF ? ah.q_base : ah.do_base;
+    const char* src = base + (size_t)grow * C::L::RS + (((ah.lane % C::L::CPR) ^ C::L::swz(row)) << 4);
+    async_copy16(src, lds_stage + (K < HALF ? 0 : C::Q_BYTES) + ah.wave * WB + S * 1024);
+    return;
+  }
   if (K < HALF) {
-    if (K == 0) async_window(lds_stage + ah.wave * WB);
+    if (K == 0 || RAGGED) async_window(lds_stage + ah.wave * WB);
     async_copy16_window<(K % HALF) * 1024>(q_src + ah.wave * WB, ah.lanes.v[K % HALF]);
   } else if (K < C::COPIES) {
-    if (K == HALF) async_window(lds_stage + C::Q_BYTES + ah.wave * WB);
+    if (K == HALF || RAGGED) async_window(lds_stage + C::Q_BYTES + ah.wave * WB);
     async_copy16_window<(K % HALF) * 1024>(do_src + ah.wave * WB, ah.lanes.v[K % HALF]);
   } else {
     async_copy16_lanes8(vec_src, lds_stage + C::Q_BYTES + C::DO_BYTES + ah.wave * 128);
@@ -424,7 +448,7 @@ __device__ __forceinline__ void dkdv_sync() {
 // step, and its last RD operand fetches already read the next entry's tile, so
 // the MFMA pipe does not drain between tiles.  On entry `op` holds the operands
 // of steps 0..RD-1 of this tile, on exit those of the next one.
-template <int D, bool MASKED>
+template <int D, bool MASKED, bool RAGGED>
 __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, const DkdvAhead& ah,
                                           bf16x8 (&op)[DkdvCfg<D>::RD], const bf16x8 (&kreg)[D / 16],
                                           const bf16x8 (&vreg)[D / 16], f32x16 (&dkacc)[D / 32],
@@ -452,6 +476,7 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
   const char* do_src = nullptr;
   const float* vec_src = nullptr;
   unsigned lds_stage = 0;
+  int i_copy = 0;
 
 #pragma unroll
   for (int x = 0; x < NX; ++x) {
@@ -480,7 +505,7 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
     // --- the workgroup step and the copies behind it
     if (x == XS) {
       dkdv_sync<D>();
-      const int i_copy = __builtin_amdgcn_readfirstlane(ah.v_copy) & 0xFFFFFF;
+      i_copy = __builtin_amdgcn_readfirstlane(ah.v_copy) & 0xFFFFFF;
       q_src = ah.q_base + (size_t)i_copy * (C::QT * D * 2);
       do_src = ah.do_base + (size_t)i_copy * (C::QT * D * 2);
       vec_src = ah.vec_src + i_copy * C::QT;
@@ -488,15 +513,15 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
     }
     if (x >= XS && x < XS + C::NC) {
       switch (x - XS) {
-        case 0: dkdv_issue_copy<D, 0>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 1: dkdv_issue_copy<D, 1>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 2: dkdv_issue_copy<D, 2>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 3: dkdv_issue_copy<D, 3>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 4: dkdv_issue_copy<D, 4>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 5: dkdv_issue_copy<D, 5>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 6: dkdv_issue_copy<D, 6>(ah, q_src, do_src, vec_src, lds_stage); break;
-        case 7: dkdv_issue_copy<D, 7>(ah, q_src, do_src, vec_src, lds_stage); break;
-        default: dkdv_issue_copy<D, 8>(ah, q_src, do_src, vec_src, lds_stage); break;
+        case 0: dkdv_issue_copy<D, 0, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 1: dkdv_issue_copy<D, 1, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 2: dkdv_issue_copy<D, 2, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 3: dkdv_issue_copy<D, 3, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 4: dkdv_issue_copy<D, 4, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 5: dkdv_issue_copy<D, 5, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 6: dkdv_issue_copy<D, 6, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        case 7: dkdv_issue_copy<D, 7, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
+        default: dkdv_issue_copy<D, 8, RAGGED>(ah, q_src, do_src, vec_src, lds_stage, i_copy); break;
       }
     }
     // --- fetch the operand of step x + RD (of the next tile once this one is used up)
@@ -538,7 +563,9 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
   }
 }
 
-template <int D>
+// RAGGED: see the forward kernel -- loops at the padded length, clamped tile copies and fragment
+// loads, guarded stores; the padding rows carry lse = +inf (P = 0), the padding keys are masked.
+template <int D, bool RAGGED>
 __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   using C = DkdvCfg<D>;
   constexpr int QT = C::QT, NDB = D / 32, NKK = D / 16;
@@ -550,17 +577,19 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, c = lane & 31;
-  const int N = a.N, H = a.H;
+  const int N = a.Np, H = a.H;            // padded length: what the loops and tables see
+  const int Nr = RAGGED ? a.N : a.Np;     // rows the tensors really have
   const int t_r = N / QT, t_c = N / C::BC;
   const int bh = unit / t_c, j_blk = unit - bh * t_c, b = bh / H;
   const int k0 = j_blk * C::BC;
   const int kw0 = k0 + wave * 32;
   const int key = kw0 + c;  // this lane's key column
+  const int key_ld = RAGGED ? min(key, Nr - 1) : key;
 
-  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * N * D;
-  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * N * D;
-  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * N * D;
-  const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * N * D;
+  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * Nr * D;
+  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * Nr * D;
+  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * Nr * D;
+  const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * Nr * D;
   const float* lsep = a.lse2 + (size_t)bh * N;
   const float* dvp = a.dvec + (size_t)bh * N;
 
@@ -575,8 +604,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   bf16x8 kreg[NKK], vreg[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    kreg[kk] = *(const bf16x8*)(kp + (size_t)key * D + kk * 16 + 8 * g);
-    vreg[kk] = *(const bf16x8*)(vp + (size_t)key * D + kk * 16 + 8 * g);
+    kreg[kk] = *(const bf16x8*)(kp + (size_t)key_ld * D + kk * 16 + 8 * g);
+    vreg[kk] = *(const bf16x8*)(vp + (size_t)key_ld * D + kk * 16 + 8 * g);
   }
   int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
   int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
@@ -613,6 +642,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
 #pragma unroll
   for (int s = 0; s < CopyLanes<D>::NINST; ++s) ah.lanes.v[s] = copy_lanes.v[s];
   ah.wave = wave;
+  ah.n_real = Nr;
+  ah.lane = lane;
   bf16x8 op[C::RD];
 
   // One pass of the tile loop over list entries [T0, T1) with the element mask compiled in or
@@ -630,7 +661,7 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     ah.stage_copy = (t + C::NSTAGE - 1) % C::NSTAGE;                                                   \
     const char* st = smem + C::STAGE_OFF + (t % C::NSTAGE) * C::STAGE;                                 \
     const int r0 = (e_cur & 0xFFFFFF) * QT;                                                            \
-    dkdv_tile<D, MASKED>(st, (const float*)(st + C::Q_BYTES + C::DO_BYTES), ah, op, kreg, vreg, dkacc, dvacc, \
+    dkdv_tile<D, MASKED, RAGGED>(st, (const float*)(st + C::Q_BYTES + C::DO_BYTES), ah, op, kreg, vreg, dkacc, dvacc, \
                          a_base, t_base0, t_base1, r0, g, sc, b_lts, b_lte, b_uts, b_ute);             \
     e_cur = __builtin_amdgcn_readfirstlane(v_next);                                                    \
   }
@@ -645,8 +676,13 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     for (int p = 0; p < C::NSTAGE - 1; ++p) {
       const int i_p = __builtin_amdgcn_readfirstlane(list[min(p, n_live - 1)]) & 0xFFFFFF;
       char* st_ = smem + C::STAGE_OFF + p * C::STAGE;
-      tile_load_async<D>(qp + (size_t)i_p * QT * D, copy_lanes, st_, wave);
-      tile_load_async<D>(dop + (size_t)i_p * QT * D, copy_lanes, st_ + C::Q_BYTES, wave);
+      if (RAGGED && (i_p + 1) * QT > Nr) {
+        tile_load_async_clamped<D>(qp, i_p * QT, Nr, st_, wave, lane);
+        tile_load_async_clamped<D>(dop, i_p * QT, Nr, st_ + C::Q_BYTES, wave, lane);
+      } else {
+        tile_load_async<D>(qp + (size_t)i_p * QT * D, copy_lanes, st_, wave);
+        tile_load_async<D>(dop + (size_t)i_p * QT * D, copy_lanes, st_ + C::Q_BYTES, wave);
+      }
       async_copy16_lanes8(my_vec + i_p * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES) + wave * 128);
     }
     // The fragment and bound loads must be complete, and known complete to the compiler, before
@@ -674,13 +710,14 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
 #undef FM_TILE_LOOP
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
-  __bf16* dkp = (__bf16*)a.dk + (size_t)bh * N * D;
-  __bf16* dvp_out = (__bf16*)a.dv + (size_t)bh * N * D;
+  __bf16* dkp = (__bf16*)a.dk + (size_t)bh * Nr * D;
+  __bf16* dvp_out = (__bf16*)a.dv + (size_t)bh * Nr * D;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int krow = kw0 + 8 * (r >> 2) + 4 * g + (r & 3);
+      if (RAGGED && krow >= Nr) continue;
       dkp[(size_t)krow * D + db * 32 + c] = (__bf16)(dkacc[db][r] * a.scale);
       dvp_out[(size_t)krow * D + db * 32 + c] = (__bf16)dvacc[db][r];
     }
@@ -691,50 +728,54 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
 using namespace fm;
 
 hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream) {
-  const long long rows = (long long)a.B * a.H * a.N;
-  const long long threads = rows * (a.d / 8);
+  const long long slices = (long long)a.B * a.H;
+  const long long threads = slices * a.Np * (a.d / 8);
   const unsigned blocks = (unsigned)((threads + 255) / 256);
   if (a.d == 128)
     hipLaunchKernelGGL(dvec_kernel<128>, dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, rows);
+                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, slices, a.N, a.Np);
   else
     hipLaunchKernelGGL(dvec_kernel<64>, dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, rows);
+                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, slices, a.N, a.Np);
   return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool RAGGED>
 static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DqCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e =
-        hipFuncSetAttribute((const void*)dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)dq_kernel<D, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dq_kernel<D>), dim3(a.slots_dq), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((dq_kernel<D, RAGGED>), dim3(a.slots_dq), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
 hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream) {
-  return a.d == 128 ? launch_dq_t<128>(a, stream) : launch_dq_t<64>(a, stream);
+  const bool ragged = a.Np != a.N;
+  if (a.d == 128) return ragged ? launch_dq_t<128, true>(a, stream) : launch_dq_t<128, false>(a, stream);
+  return ragged ? launch_dq_t<64, true>(a, stream) : launch_dq_t<64, false>(a, stream);
 }
 
-template <int D>
+template <int D, bool RAGGED>
 static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DkdvCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e =
-        hipFuncSetAttribute((const void*)dkdv_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)dkdv_kernel<D, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dkdv_kernel<D>), dim3(a.slots_dkdv), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED>), dim3(a.slots_dkdv), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
 hipError_t fm_launch_bwd_dkdv(const FmBwdArgs& a, hipStream_t stream) {
-  return a.d == 128 ? launch_dkdv_t<128>(a, stream) : launch_dkdv_t<64>(a, stream);
+  const bool ragged = a.Np != a.N;
+  if (a.d == 128) return ragged ? launch_dkdv_t<128, true>(a, stream) : launch_dkdv_t<128, false>(a, stream);
+  return ragged ? launch_dkdv_t<64, true>(a, stream) : launch_dkdv_t<64, false>(a, stream);
 }

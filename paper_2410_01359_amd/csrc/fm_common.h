@@ -221,6 +221,24 @@ __device__ __forceinline__ void tile_load_async(const __bf16* tile_src, const Co
   }
 }
 
+// The same tile copy for a tile whose last rows lie past the end of the tensor (sequence length
+// not a multiple of the tile): every lane clamps its source row to the last real one, so all
+// reads stay in bounds; what lands in the extra rows is finite and the mask keeps it out of the
+// result.  tensor_bh is row 0 of the (batch, head) slice, row0 the tile's first row.
+template <int D>
+__device__ __forceinline__ void tile_load_async_clamped(const __bf16* tensor_bh, int row0, int n_real,
+                                                        const char* lds_tile, int wave, int lane) {
+  using L = TileLayout<D>;
+  constexpr int RPI = 64 / L::CPR, NINST = 16 / RPI;
+#pragma unroll
+  for (int s = 0; s < NINST; ++s) {
+    const int row = wave * 16 + s * RPI + lane / L::CPR;
+    const int grow = min(row0 + row, n_real - 1);
+    const char* src = (const char*)tensor_bh + (size_t)grow * L::RS + (((lane % L::CPR) ^ L::swz(row)) << 4);
+    async_copy16(src, lds_address(lds_tile) + wave * 16 * L::RS + s * 1024);
+  }
+}
+
 // Force a value that was fetched with an ordinary global load to be complete
 // (and known complete to the compiler) at this point.  The tile loops issue
 // their async copies behind the compiler's back; if the first use of such a

@@ -163,7 +163,11 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
   }
 }
 
-template <int D>
+// RAGGED: the sequence length is not a multiple of 128.  The loops then run at the padded length
+// Np (tables, lists and the padded bound vectors are built for it; the padding columns are masked
+// for every row), tile copies that reach past row N clamp their source rows, and rows >= N are
+// computed but not stored.
+template <int D, bool RAGGED>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   using C = FwdCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16, QB = 1;
@@ -174,15 +178,16 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, c = lane & 31;
-  const int N = a.N, H = a.H;
+  const int N = a.Np, H = a.H;            // padded length: what the loops and tables see
+  const int Nr = RAGGED ? a.N : a.Np;     // rows the tensors really have
   const int t_r = N / C::BR, t_c = N / KT;
   const int bh = unit / t_r, i_blk = unit - bh * t_r, b = bh / H;
   const int q0 = i_blk * C::BR;
   const int qw0 = q0 + wave * 32;
 
-  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * N * D;
-  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * N * D;
-  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * N * D;
+  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * Nr * D;
+  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * Nr * D;
+  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * Nr * D;
   const int* table = a.minmax + (size_t)b * 8 * t_c;
   // lanes of wave 0 copy the four bound slices of a partially masked tile: lane l moves
   // 16 bytes of vector l / 16
@@ -201,7 +206,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   // Q fragments (B operand of S^T = K Q^T): lane holds Q[row c][16 kk + 8 g ..+7].
   bf16x8 qreg[NKK];
 #pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) qreg[kk] = *(const bf16x8*)(qp + (size_t)(qw0 + c) * D + kk * 16 + 8 * g);
+  for (int kk = 0; kk < NKK; ++kk)
+    qreg[kk] = *(const bf16x8*)(qp + (size_t)(RAGGED ? min(qw0 + c, Nr - 1) : qw0 + c) * D + kk * 16 + 8 * g);
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) settle(qreg[kk]);
 
@@ -227,13 +233,23 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
 
   // Asynchronous copies of list entry ENTRY: its K tile into K stage KBUF / its V tile (and, if the
   // workgroup's tile is partially masked, its bound slices) into V stage VBUF.
-#define FM_LOAD_K(ENTRY, KBUF) \
-  tile_load_async<D>(kp + (size_t)entry_block(ENTRY, chunk) * KT * D, copy_lanes, smem + C::K_OFF + (KBUF) * C::K_BYTES, wave)
+#define FM_LOAD_K(ENTRY, KBUF)                                                                   \
+  {                                                                                              \
+    const int j_ = entry_block(ENTRY, chunk);                                                    \
+    char* st_ = smem + C::K_OFF + (KBUF) * C::K_BYTES;                                           \
+    if (RAGGED && (j_ + 1) * KT > Nr)                                                            \
+      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane);                              \
+    else                                                                                         \
+      tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                       \
+  }
 #define FM_LOAD_V(ENTRY, VBUF)                                                                   \
   {                                                                                              \
     const int j_ = entry_block(ENTRY, chunk);                                                    \
     char* st_ = smem + C::V_OFF + (VBUF) * C::VSTAGE;                                            \
-    tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                         \
+    if (RAGGED && (j_ + 1) * KT > Nr)                                                            \
+      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_, wave, lane);                              \
+    else                                                                                         \
+      tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                       \
     if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                       \
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::V_BYTES));                            \
   }
@@ -294,23 +310,25 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
 #undef FM_LOAD_V
 
   // epilogue: O / l, lse = m + log(l)   (m, l in the log2 domain)
-  __bf16* op = (__bf16*)a.out + (size_t)bh * N * D;
-  float* lp = a.lse + (size_t)bh * N;
+  __bf16* op = (__bf16*)a.out + (size_t)bh * Nr * D;
+  float* lp = a.lse + (size_t)bh * Nr;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const float lt = l_run + partner32(l_run);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int row = qw0 + qb * 32 + c;
+    if (!RAGGED || row < Nr) {
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+      for (int db = 0; db < NDB; ++db)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        bf16x4 o4;
+        for (int rq = 0; rq < 4; ++rq) {
+          bf16x4 o4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][rq * 4 + e] * inv);
-        *(bf16x4*)(op + (size_t)row * D + db * 32 + 8 * rq + 4 * g) = o4;
-      }
-    if (g == 0) lp[row] = lt > 0.f ? (m_run + fast_log2(lt)) * kLn2 : -INFINITY;
+          for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][rq * 4 + e] * inv);
+          *(bf16x4*)(op + (size_t)row * D + db * 32 + 8 * rq + 4 * g) = o4;
+        }
+      if (g == 0) lp[row] = lt > 0.f ? (m_run + fast_log2(lt)) * kLn2 : -INFINITY;
+    }
   }
 }
 
@@ -318,22 +336,23 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
 
 using namespace fm;
 
-template <int D>
+template <int D, bool RAGGED>
 static hipError_t launch_fwd_t(const FmFwdArgs& a, hipStream_t stream) {
   using C = FwdCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fwd_kernel<D>), dim3(a.slots), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((fwd_kernel<D, RAGGED>), dim3(a.slots), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
 hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream) {
   static_assert(FM_FWD_BR == 128, "forward row block");
-  if (a.d == 128) return launch_fwd_t<128>(a, stream);
-  return launch_fwd_t<64>(a, stream);
+  const bool ragged = a.Np != a.N;
+  if (a.d == 128) return ragged ? launch_fwd_t<128, true>(a, stream) : launch_fwd_t<128, false>(a, stream);
+  return ragged ? launch_fwd_t<64, true>(a, stream) : launch_fwd_t<64, false>(a, stream);
 }

@@ -1,6 +1,8 @@
 // Preprocessing (Section 4.2): per key-block min/max of the four bound vectors,
 // the exported tile-class dump (Equation 4), and the per-unit work counts the
 // launch order is built from.
+#include <climits>
+
 #include "fm_common.h"
 #include "fm_kernels.h"
 
@@ -60,6 +62,23 @@ __global__ __launch_bounds__(256) void classify_kernel(const int* __restrict__ m
   const int r0 = i * block_r;
   const int r1 = min(r0 + block_r, n);
   cls[((size_t)b * t_r + i) * t_c + j] = (uint8_t)classify_tile(r0, r1, t);
+}
+
+// Padded copies of the bound vectors for a sequence length that is not a multiple of 128: the
+// columns past the end get an interval that masks every row (LTS = INT_MIN, LTE = INT_MAX), so
+// the tile loops treat them like any other masked key and every vector read stays in bounds.
+__global__ __launch_bounds__(256) void pad_bounds_kernel(const int* __restrict__ lts, const int* __restrict__ lte,
+                                                         const int* __restrict__ uts, const int* __restrict__ ute,
+                                                         int batch, int n, int np, int* __restrict__ padded) {
+  const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= (long long)batch * np) return;
+  const int b = (int)(gid / np), j = (int)(gid % np);
+  const size_t plane = (size_t)batch * np, src = (size_t)b * n + j;
+  const bool in = j < n;
+  padded[0 * plane + gid] = in ? lts[src] : INT_MIN;
+  padded[1 * plane + gid] = in ? lte[src] : INT_MAX;
+  padded[2 * plane + gid] = in ? uts[src] : 0;
+  padded[3 * plane + gid] = in ? ute[src] : 0;
 }
 
 // Work of one row block = number of key blocks that are not fully masked, and
@@ -203,6 +222,14 @@ hipError_t fm_launch_preprocess(const int* lts, const int* lte, const int* uts, 
   const int total = B * t_c;
   hipLaunchKernelGGL(preprocess_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, lts, lte, uts, ute, N, block_c,
                      t_c, total, minmax);
+  return hipGetLastError();
+}
+
+hipError_t fm_launch_pad_bounds(const int* lts, const int* lte, const int* uts, const int* ute, int B, int N, int Np,
+                                int* padded, hipStream_t stream) {
+  const long long total = (long long)B * Np;
+  hipLaunchKernelGGL(pad_bounds_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, lts, lte, uts, ute,
+                     B, N, Np, padded);
   return hipGetLastError();
 }
 

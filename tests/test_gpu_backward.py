@@ -44,6 +44,16 @@ def test_backward_small(kind, N, d):
     compare_all(w, *run_fwd_bwd(w), f"{kind} N={N} d={d}")
 
 
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("N,d", [(1, 64), (77, 128), (129, 64), (200, 128), (333, 64), (1000, 128)])
+def test_backward_ragged_lengths(kind, N, d):
+    """Sequence lengths that are not a multiple of the tile sizes (or of anything)."""
+    if N < 8 and kind not in ("full", "causal", "random_intervals"):
+        pytest.skip("family needs a few rows")
+    w = workloads.small_workload(kind, N, seed=57 + N + d, B=2, H=2, d=d)
+    compare_all(w, *run_fwd_bwd(w), f"{kind} N={N} d={d}")
+
+
 def test_backward_config1_all_heads():
     w = workloads.config("1")
     compare_all(w, *run_fwd_bwd(w), "config 1")

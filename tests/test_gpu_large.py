@@ -29,7 +29,7 @@ def _rounded(x_f32: np.ndarray) -> np.ndarray:
     return workloads.bf16_bits_to_f32(workloads.to_bf16_bits(x_f32)).astype(np.float64)
 
 
-@pytest.mark.parametrize("N,d", [(262144, 64), (131072, 128)])
+@pytest.mark.parametrize("N,d", [(262144, 64), (131072, 128), (10001, 128), (4099, 64)])
 def test_causal_zero_query_closed_forms(N, d):
     import paper_2410_01359_amd as fm
     rng = np.random.Generator(np.random.PCG64(991 + N + d))
