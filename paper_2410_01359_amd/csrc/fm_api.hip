@@ -53,7 +53,7 @@ PassSpace pass_space(int B, int H, int N, int block_r, int block_c, bool row_uni
   s.work = align_up(s.minmax + (size_t)B * 8 * t_c * 4, 256);
   s.range = align_up(s.work + (size_t)B * per * 4, 256);
   s.order = align_up(s.range + (size_t)B * per * 8, 256);
-  s.total = align_up(s.order + (size_t)fm_order_slots((int)((size_t)B * H * per)) * 4, 256);
+  s.total = align_up(s.order + fm_order_bytes((int)((size_t)B * H * per)), 256);
   return s;
 }
 
@@ -161,7 +161,7 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   FmFwdArgs a;
   a.q = q; a.k = k; a.v = v;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
-  a.minmax = minmax; a.order = order; a.range = range;
+  a.minmax = minmax; a.order = order;
   a.out = out; a.lse = lse; a.scale = scale;
   a.B = B; a.H = H; a.N = N; a.Np = Np; a.d = d;
   a.slots = fm_order_slots(B * H * (Np / FM_FWD_BR));
@@ -202,9 +202,8 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   FmBwdArgs a;
   a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
-  a.minmax_dq = (int*)(ws + sq.minmax); a.order_dq = (int*)(ws + sq.order); a.range_dq = (int*)(ws + sq.range);
+  a.minmax_dq = (int*)(ws + sq.minmax); a.order_dq = (int*)(ws + sq.order);
   a.minmax_dkdv = (int*)(ws + skv.minmax); a.order_dkdv = (int*)(ws + skv.order);
-  a.range_dkdv = (int*)(ws + skv.range);
   a.dvec = (float*)(ws + skv.total);
   a.lse2 = (float*)(ws + skv.total + align_up((size_t)B * H * Np * 4, 256));
   a.dq = dq; a.dk = dk; a.dv = dv; a.scale = scale;

@@ -75,7 +75,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  const int unit = a.order_dq[blockIdx.x];
+  const i32x4 rec = queue_take(a.order_dq, a.slots_dq, (int*)(smem + C::CNT_OFF) + 8);
+  const int unit = rec[0], j_lo = rec[1], j_hi = rec[2];
   if (unit < 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -155,7 +156,6 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   }
 
   // only the key blocks [j_lo, j_hi) can be live for this row block (found by the work pre-pass)
-  const int j_lo = a.range_dq[2 * ((size_t)b * t_r + i_blk)], j_hi = a.range_dq[2 * ((size_t)b * t_r + i_blk) + 1];
   for (int chunk = j_lo; chunk < j_hi; chunk += C::LIST_CAP) {
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, j_hi), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
@@ -572,7 +572,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   static_assert(QT == 64, "the tile loop is written for two 32-row blocks per tile");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  const int unit = a.order_dkdv[blockIdx.x];
+  const i32x4 rec = queue_take(a.order_dkdv, a.slots_dkdv, (int*)(smem + C::CNT_OFF) + 8);
+  const int unit = rec[0], i_lo = rec[1], i_hi = rec[2];
   if (unit < 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -594,9 +595,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const float* dvp = a.dvec + (size_t)bh * N;
 
   // What the list of live row blocks needs comes first, so that its latency is not queued
-  // behind the fragment loads below: the block's min/max values and its live row-block range.
+  // behind the fragment loads below: the block's min/max values.
   const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
-  const int i_lo = a.range_dkdv[2 * ((size_t)b * t_c + j_blk)], i_hi = a.range_dkdv[2 * ((size_t)b * t_c + j_blk) + 1];
 
   // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T) and the four
   // bounds of this lane's key, which stay in registers (Algorithm 2 loads them once per key
@@ -750,7 +750,7 @@ static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dq_kernel<D, RAGGED>), dim3(a.slots_dq), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((dq_kernel<D, RAGGED>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
@@ -770,7 +770,7 @@ static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED>), dim3(a.slots_dkdv), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED>), dim3(fm_launch_grid(a.slots_dkdv)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fm_kernels.h"
+
 namespace fm {
 
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -255,6 +257,43 @@ __device__ __forceinline__ void settle(T& x) {
 __device__ __forceinline__ int opaque(int x) {
   asm volatile("" : "+v"(x));
   return x;
+}
+
+// Unit queues.  Workgroup x draws a ticket from queue x % FM_QUEUES (ticket t of queue g is slot
+// t * FM_QUEUES + g of the launch order); when that queue is used up it draws from the queue that
+// has most left, and when all are used up it gets nothing.  Returns the slot record, wave-uniform,
+// with unit = -1 for "nothing".  One barrier; lds_word is a scratch word in LDS.  The counters sit
+// behind the slot records and are zeroed by the launch-order kernel of every call.
+__device__ __forceinline__ i32x4 queue_take(int* order, int slots, int* lds_word) {
+  if (threadIdx.x == 0) {
+    int* counters = order + 4 * (size_t)slots;
+    const int per_queue = slots / FM_QUEUES;
+    int q = blockIdx.x % FM_QUEUES;
+    int t = atomicAdd(counters + q, 1);
+    for (int attempt = 0; t >= per_queue && attempt < FM_QUEUES; ++attempt) {
+      int best = -1, best_left = 0;
+      for (int g = 0; g < FM_QUEUES; ++g) {
+        const int left = per_queue - __hip_atomic_load(counters + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left > best_left) {
+          best_left = left;
+          best = g;
+        }
+      }
+      if (best < 0) break;
+      q = best;
+      t = atomicAdd(counters + q, 1);
+    }
+    *lds_word = t < per_queue ? t * FM_QUEUES + q : -1;
+  }
+  __syncthreads();
+  const int slot = __builtin_amdgcn_readfirstlane(*lds_word);
+  i32x4 rec = {-1, 0, 0, 0};
+  if (slot >= 0) {
+    const i32x4 r = *(const i32x4*)(order + 4 * (size_t)slot);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rec[e] = __builtin_amdgcn_readfirstlane(r[e]);
+  }
+  return rec;
 }
 
 // Ordered compaction shared by the tile loops: every thread of a 256-thread

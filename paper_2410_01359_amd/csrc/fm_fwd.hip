@@ -173,7 +173,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16, QB = 1;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  const int unit = a.order[blockIdx.x];
+  const i32x4 rec = queue_take(a.order, a.slots, (int*)(smem + C::CNT_OFF) + 8);
+  const int unit = rec[0], j_lo = rec[1], j_hi = rec[2];
   if (unit < 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -270,7 +271,6 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   }
 
   // only the key blocks [j_lo, j_hi) can be live for this row block (found by the work pre-pass)
-  const int j_lo = a.range[2 * ((size_t)b * t_r + i_blk)], j_hi = a.range[2 * ((size_t)b * t_r + i_blk) + 1];
   for (int chunk = j_lo; chunk < j_hi; chunk += C::LIST_CAP) {
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, j_hi), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
@@ -346,7 +346,7 @@ static hipError_t launch_fwd_t(const FmFwdArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fwd_kernel<D, RAGGED>), dim3(a.slots), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((fwd_kernel<D, RAGGED>), dim3(fm_launch_grid(a.slots)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 

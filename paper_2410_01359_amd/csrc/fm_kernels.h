@@ -3,8 +3,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-// Number of launch slots for `units` work units: 8 interleaved groups.
-inline int fm_order_slots(int units) { return ((units + 7) / 8) * 8; }
+// The tile loops draw their work units from FM_QUEUES interleaved queues (one per XCD).
+constexpr int FM_QUEUES = 8;
+// Number of queue slots for `units` work units.
+inline int fm_order_slots(int units) { return ((units + FM_QUEUES - 1) / FM_QUEUES) * FM_QUEUES; }
+// Bytes of a pass's queue area: one 16-byte record per slot, then the FM_QUEUES queue counters.
+inline size_t fm_order_bytes(int units) { return (size_t)fm_order_slots(units) * 16 + FM_QUEUES * 4; }
+// Workgroups of a tile-loop launch: one per slot plus a reserve of one eighth, through which the
+// XCDs that finish their own queue early take units from the others (a workgroup that finds
+// every queue empty ends at once).
+inline int fm_launch_grid(int slots) { return slots + fm_order_slots(slots / 8); }
 
 struct FmShape {
   int B, H, N, d;
@@ -23,7 +31,8 @@ hipError_t fm_launch_pad_bounds(const int* lts, const int* lte, const int* uts, 
 hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int block_c, uint8_t* cls,
                               hipStream_t stream);
 // work: int[B * T_r] (resp. B * T_c); range: int[2 * B * T] = first live block and one past the
-// last live block of every unit (0, 0 if none); order: int[fm_order_slots(B*H*T)].
+// last live block of every unit (0, 0 if none); order: fm_order_bytes(B*H*T) bytes = the slot
+// records {unit, first, last, 0} followed by the queue counters (zeroed here).
 hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream);
 hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
@@ -36,8 +45,8 @@ struct FmFwdArgs {
   const void *q, *k, *v;
   const int *lts, *lte, *uts, *ute;   // [B][Np]
   const int* minmax;  // [B][8][T_c] at FM_FWD_BC
-  const int* order;   // launch slots -> unit (b*H + h)*T_r + i, or -1
-  const int* range;   // [B][T_r][2]: key blocks [first, last) outside of which the row block is fully masked
+  int* order;         // queue slots {unit (b*H + h)*T_r + i or -1, first live key block, last + 1, 0}, then the
+                      // queue counters; a row block is fully masked outside [first, last)
   void* out;
   float* lse;
   float scale;
@@ -51,11 +60,9 @@ struct FmBwdArgs {
   const float* lse;
   const int *lts, *lte, *uts, *ute;
   const int* minmax_dq;    // [B][8][T_c] at FM_DQ_BC
-  const int* order_dq;
-  const int* range_dq;     // [B][T_r][2] key-block range of each row block
+  int* order_dq;           // queue slots and counters of the dQ pass (live key-block range per row block)
   const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
-  const int* order_dkdv;
-  const int* range_dkdv;   // [B][T_c][2] row-block range of each key block
+  int* order_dkdv;         // queue slots and counters of the dK/dV pass (live row-block range per key block)
   float* dvec;             // -D = -rowsum(dO o O), [B,H,Np] (stored negated; 0 in the padding)
   float* lse2;             // lse * log2(e), +inf where lse = -inf and in the padding, [B,H,Np]
   void *dq, *dk, *dv;

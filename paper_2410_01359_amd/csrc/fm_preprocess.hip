@@ -144,28 +144,35 @@ __global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ m
   }
 }
 
-// Launch order (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8
-// and workgroups start in index order as slots free up.  Units are therefore
-// dealt into 8 groups (one per XCD: by head when the head count is a multiple
-// of 8, so that the units sharing one head's K/V also share one L2), each
-// group is sorted heaviest first (work quantised to 512 levels), and the
-// groups are interleaved: order[8*s + g] = s-th heaviest unit of group g.
-// In-order dispatch of that list is longest-job-first list scheduling per XCD.
-// Slots with no unit hold -1.  Single workgroup of 1024 threads.
+// Launch order (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8.
+// Units are dealt into 8 queues (one per XCD: by head when the head count is a
+// multiple of 8, so that the units sharing one head's K/V also share one L2),
+// each queue is sorted heaviest first (work quantised to 512 levels), and the
+// queues are interleaved: slot 8*s + g = s-th heaviest unit of queue g.  A
+// workgroup draws the next ticket of its XCD's queue when it starts, so every
+// queue is worked off longest-job-first; the launch holds more workgroups than
+// there are slots, and a workgroup that finds its own queue empty draws from the
+// queue that has most left.  (The XCDs do not run at the same speed: with equal
+// shares the slowest one finishes about a tenth later than the fastest.)
+// A slot is the record {unit, first live block, one past the last live block, 0},
+// so a workgroup learns all it needs to start from one 16-byte load; slots with
+// no unit hold unit = -1.  The kernel also zeroes the 8 queue counters behind
+// the slots.  Single workgroup of 1024 threads.
 constexpr int kLevels = 512;
-constexpr int kGroups = 8;
+constexpr int kGroups = FM_QUEUES;
 
-// work is indexed [batch row][block]; a unit is (batch row, head, block).
-__global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ work, int batch, int heads,
-                                                     int units_per_bh, int max_work, int slots,
-                                                     int* __restrict__ order) {
+// work and range are indexed [batch row][block]; a unit is (batch row, head, block).
+__global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ work, const int* __restrict__ range,
+                                                     int batch, int heads, int units_per_bh, int max_work, int slots,
+                                                     i32x4* __restrict__ order, int* __restrict__ counters) {
   __shared__ int hist[kGroups * kLevels];
   __shared__ int wave_sum[16];
   const int tid = threadIdx.x;
   const int total_units = batch * heads * units_per_bh;
   const bool by_head = ((batch * heads) % kGroups) == 0;
   for (int w = tid; w < kGroups * kLevels; w += 1024) hist[w] = 0;
-  for (int s = tid; s < slots; s += 1024) order[s] = -1;
+  for (int s = tid; s < slots; s += 1024) order[s] = i32x4{-1, 0, 0, 0};
+  if (tid < kGroups) counters[tid] = 0;
   __syncthreads();
   auto key_of = [&](int u) {
     const int g = by_head ? (u / units_per_bh) % kGroups : u % kGroups;
@@ -208,7 +215,8 @@ __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ wor
     const int g = key / kLevels;
     const int pos = atomicAdd(&hist[key], 1) - group_start[g];
     const int slot = pos * kGroups + g;
-    if (slot < slots) order[slot] = u;
+    const int ru = (u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh;
+    if (slot < slots) order[slot] = i32x4{u, range[2 * ru], range[2 * ru + 1], 0};
   }
 }
 
@@ -249,8 +257,9 @@ hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block
   const int total = B * t_r;
   hipLaunchKernelGGL(row_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
-  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, B, H, t_r, t_c,
-                     fm_order_slots(B * H * t_r), order);
+  const int slots = fm_order_slots(B * H * t_r);
+  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, range, B, H, t_r, t_c, slots, (i32x4*)order,
+                     order + 4 * (size_t)slots);
   return hipGetLastError();
 }
 
@@ -261,7 +270,8 @@ hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block
   const int total = B * t_c;
   hipLaunchKernelGGL(col_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
-  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, B, H, t_c, t_r,
-                     fm_order_slots(B * H * t_c), order);
+  const int slots = fm_order_slots(B * H * t_c);
+  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, range, B, H, t_c, t_r, slots, (i32x4*)order,
+                     order + 4 * (size_t)slots);
   return hipGetLastError();
 }
