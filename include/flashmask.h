@@ -107,6 +107,42 @@ int flashmask_bwd(const void* q, const void* k, const void* v,
                   int B, int H, int N, int d,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Layout of a bf16 tensor indexed [batch][head][row][d] for the *_ex entry points: distances, in
+ * ELEMENTS, between consecutive batches, heads and rows; d itself is contiguous.  A tensor stored
+ * [B,N,H,d] has {N*H*d, d, H*d}; a slice of a packed [B,N,3,H,d] projection has {N*3*H*d, d, 3*H*d}.
+ * Every stride must be a multiple of 8 (16-byte vectors along d), row >= d and < 2^24
+ * (FM_ERR_ALIGN / FM_ERR_SHAPE otherwise).
+ */
+typedef struct {
+  int64_t batch, head, row;
+} flashmask_strides;
+
+/*
+ * The forward and backward passes above for tensors that are not contiguous [B,H,N,d], and for
+ * grouped K/V heads (the inference shape of the paper's Appendix, 32 query heads on 8 K/V heads):
+ * k, v (and dk, dv) have H_kv heads, H % H_kv == 0, and query head h attends to K/V head
+ * h / (H / H_kv); dk, dv are summed over the query heads of a group.  Same arithmetic, same
+ * workspace size (flashmask_workspace_bytes with H), same error behaviour; lse stays fp32
+ * contiguous [B,H,N].  Outputs must not overlap inputs or each other.
+ *   forward : sq, sk, sv, so describe q, k, v, out
+ *   backward: strides[8] describe q, k, v, out, dout, dq, dk, dv in this order
+ */
+int flashmask_fwd_ex(const void* q, const void* k, const void* v,
+                     const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                     float scale, void* out, float* lse,
+                     int B, int H, int H_kv, int N, int d,
+                     const flashmask_strides* sq, const flashmask_strides* sk,
+                     const flashmask_strides* sv, const flashmask_strides* so,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+int flashmask_bwd_ex(const void* q, const void* k, const void* v,
+                     const void* out, const float* lse, const void* dout,
+                     const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                     float scale, void* dq, void* dk, void* dv,
+                     int B, int H, int H_kv, int N, int d,
+                     const flashmask_strides* strides,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of scratch a call of the given pass needs (FM_PASS_FWD or FM_PASS_BWD).
  * Returns 0 for an invalid shape or pass.  Host-only, no device work. */
 size_t flashmask_workspace_bytes(int pass, int B, int H, int N, int d);

@@ -20,6 +20,11 @@ class FlashMaskError(RuntimeError):
     pass
 
 
+class Strides(ctypes.Structure):
+    """flashmask_strides: element strides of a tensor indexed [batch][head][row][d]."""
+    _fields_ = [("batch", ctypes.c_int64), ("head", ctypes.c_int64), ("row", ctypes.c_int64)]
+
+
 def library_path() -> str:
     return os.path.join(_HERE, "libflashmask.so")
 
@@ -40,6 +45,11 @@ def load_library() -> ctypes.CDLL:
     lib.flashmask_fwd.argtypes = [vp, vp, vp, ip, ip, ip, ip, f, vp, fp, i, i, i, i, vp, sz, vp]
     lib.flashmask_bwd.restype = i
     lib.flashmask_bwd.argtypes = [vp, vp, vp, vp, fp, vp, ip, ip, ip, ip, f, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    sp = ctypes.POINTER(Strides)
+    lib.flashmask_fwd_ex.restype = i
+    lib.flashmask_fwd_ex.argtypes = [vp, vp, vp, ip, ip, ip, ip, f, vp, fp, i, i, i, i, i, sp, sp, sp, sp, vp, sz, vp]
+    lib.flashmask_bwd_ex.restype = i
+    lib.flashmask_bwd_ex.argtypes = [vp, vp, vp, vp, fp, vp, ip, ip, ip, ip, f, vp, vp, vp, i, i, i, i, i, sp, vp, sz, vp]
     lib.flashmask_workspace_bytes.restype = sz
     lib.flashmask_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.flashmask_preprocess.restype = i
@@ -155,4 +165,67 @@ def flashmask_bwd(q, k, v, out, lse, dout, lts, lte, uts, ute, scale: float, wor
                                         dout.data_ptr(), lts.data_ptr(), lte.data_ptr(), uts.data_ptr(),
                                         ute.data_ptr(), float(scale), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                         B, H, N, d, ws.data_ptr(), ws.numel(), _stream()), "flashmask_bwd")
+    return dq, dk, dv
+
+
+def _view(t: torch.Tensor, name: str) -> Strides:
+    """Strides of a bf16 tensor indexed [B, heads, N, d]; d must be contiguous."""
+    if not t.is_cuda:
+        raise FlashMaskError(f"{name} must live on the GPU")
+    if t.dtype != torch.bfloat16:
+        raise FlashMaskError(f"{name} must be bfloat16, got {t.dtype}")
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise FlashMaskError(f"{name} must be indexed [B, heads, N, d] with d contiguous")
+    return Strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def flashmask_fwd_ex(q, k, v, lts, lte, uts, ute, scale: float, workspace: torch.Tensor | None = None):
+    """Forward for tensors of any strides (indexed [B,heads,N,d], d contiguous: pass `x.transpose(1, 2)` of
+    a [B,N,H,d] tensor) and for k, v with fewer heads than q (H % H_kv == 0).  Returns out (bf16, laid
+    out like q) and lse (fp32 [B,H,N])."""
+    sq, sk, sv = _view(q, "q"), _view(k, "k"), _view(v, "v")
+    for t, n in zip((lts, lte, uts, ute), ("lts", "lte", "uts", "ute")):
+        _dev(t, torch.int32, n)
+    B, H, N, d = q.shape
+    Hk = k.shape[1]
+    if tuple(k.shape) != (B, Hk, N, d) or v.shape != k.shape or any(tuple(x.shape) != (B, N) for x in (lts, lte, uts, ute)):
+        raise FlashMaskError("shape mismatch: q [B,H,N,d]; k,v [B,H_kv,N,d]; lts,lte,uts,ute [B,N]")
+    need = flashmask_workspace_bytes(FM_PASS_FWD, B, H, N, d)
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    out = torch.empty_like(q)
+    so = _view(out, "out")
+    lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    _check(load_library().flashmask_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), lts.data_ptr(), lte.data_ptr(),
+                                           uts.data_ptr(), ute.data_ptr(), float(scale), out.data_ptr(),
+                                           lse.data_ptr(), B, H, Hk, N, d, ctypes.byref(sq), ctypes.byref(sk),
+                                           ctypes.byref(sv), ctypes.byref(so), ws.data_ptr(), ws.numel(), _stream()),
+           "flashmask_fwd_ex")
+    return out, lse
+
+
+def flashmask_bwd_ex(q, k, v, out, lse, dout, lts, lte, uts, ute, scale: float,
+                     workspace: torch.Tensor | None = None):
+    """Backward for tensors of any strides and grouped K/V heads (see flashmask_fwd_ex).  Returns dq (laid
+    out like q), dk and dv (laid out like k and v, summed over the query heads of each group)."""
+    tensors = (q, k, v, out, dout)
+    names = ("q", "k", "v", "out", "dout")
+    st = [_view(t, n) for t, n in zip(tensors, names)]
+    _dev(lse, torch.float32, "lse")
+    for t, n in zip((lts, lte, uts, ute), ("lts", "lte", "uts", "ute")):
+        _dev(t, torch.int32, n)
+    B, H, N, d = q.shape
+    Hk = k.shape[1]
+    if tuple(k.shape) != (B, Hk, N, d) or v.shape != k.shape or out.shape != q.shape or dout.shape != q.shape or \
+            tuple(lse.shape) != (B, H, N) or any(tuple(x.shape) != (B, N) for x in (lts, lte, uts, ute)):
+        raise FlashMaskError("shape mismatch")
+    need = flashmask_workspace_bytes(FM_PASS_BWD, B, H, N, d)
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    st += [_view(dq, "dq"), _view(dk, "dk"), _view(dv, "dv")]
+    arr = (Strides * 8)(*st)
+    _check(load_library().flashmask_bwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                           dout.data_ptr(), lts.data_ptr(), lte.data_ptr(), uts.data_ptr(),
+                                           ute.data_ptr(), float(scale), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                           B, H, Hk, N, d, arr, ws.data_ptr(), ws.numel(), _stream()),
+           "flashmask_bwd_ex")
     return dq, dk, dv

@@ -34,6 +34,21 @@ int check_shape(int B, int H, int N, int d) {
   return FM_OK;
 }
 
+// Stride record of a contiguous [B, heads, N, d] tensor.
+FmStride dense(int heads, int N, int d) { return FmStride{(long long)heads * N * d, (long long)N * d, (long long)d}; }
+FmStride to_kernel(const flashmask_strides& s) { return FmStride{s.batch, s.head, s.row}; }
+
+// Strides the kernels can address: 16-byte vectors along d stay aligned (multiples of 8 elements),
+// rows do not overlap (row >= d) and 64 rows fit a 32-bit byte offset; a size-1 axis may have any stride.
+int check_strides(const flashmask_strides* s, int B, int heads, int N, int d) {
+  if (!s) return FM_ERR_NULL;
+  if (s->batch % 8 || s->head % 8 || s->row % 8) return FM_ERR_ALIGN;
+  if (s->row < d || s->row >= (1ll << 24)) return FM_ERR_SHAPE;
+  if (s->batch < 0 || s->head < 0) return FM_ERR_SHAPE;
+  if ((B > 1 && s->batch == 0) || (heads > 1 && s->head == 0)) return FM_ERR_SHAPE;
+  return FM_OK;
+}
+
 // The tile loops work at the sequence length rounded up to a multiple of 128; a sequence that is
 // not such a multiple gets padded copies of its bound vectors at the front of the workspace.
 inline int padded_len(int N) { return (N + 127) / 128 * 128; }
@@ -124,9 +139,10 @@ int flashmask_classify(const int32_t* minmax, int B, int N, int block_r, int blo
   return e == hipSuccess ? FM_OK : hip_fail(e);
 }
 
-int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
-                  const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H, int N,
-                  int d, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int fwd_impl(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
+                    const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H, int Hk,
+                    int N, int d, const FmStride* st /* q, k, v, out; NULL = contiguous, Hk == H */, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
   if (!q || !k || !v || !lts || !lte || !uts || !ute || !out || !lse) return FM_ERR_NULL;
   if (int rc = check_shape(B, H, N, d)) return rc;
   if (!(scale > 0.f) || !(scale < 3.0e38f)) return FM_ERR_ARG;
@@ -165,16 +181,44 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
   a.out = out; a.lse = lse; a.scale = scale;
   a.B = B; a.H = H; a.N = N; a.Np = Np; a.d = d;
   a.slots = fm_order_slots(B * H * (Np / FM_FWD_BR));
+  a.general = st != nullptr;
+  a.Hk = Hk;
+  if (st) { a.sq = st[0]; a.sk = st[1]; a.sv = st[2]; a.so = st[3]; }
+  else { a.sq = a.so = dense(H, N, d); a.sk = a.sv = dense(Hk, N, d); }
   e = fm_launch_fwd(a, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(2, stream);
   return FM_OK;
 }
 
-int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse, const void* dout,
-                  const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute, float scale,
-                  void* dq, void* dk, void* dv, int B, int H, int N, int d, void* workspace, size_t workspace_bytes,
-                  void* hip_stream) {
+int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
+                  const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H, int N,
+                  int d, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return fwd_impl(q, k, v, lts, lte, uts, ute, scale, out, lse, B, H, H, N, d, nullptr, workspace, workspace_bytes,
+                  hip_stream);
+}
+
+int flashmask_fwd_ex(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
+                     const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H,
+                     int H_kv, int N, int d, const flashmask_strides* sq, const flashmask_strides* sk,
+                     const flashmask_strides* sv, const flashmask_strides* so, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  if (int rc = check_shape(B, H, N, d)) return rc;
+  if (H_kv <= 0 || H % H_kv != 0) return FM_ERR_SHAPE;
+  if (int rc = check_strides(sq, B, H, N, d)) return rc;
+  if (int rc = check_strides(sk, B, H_kv, N, d)) return rc;
+  if (int rc = check_strides(sv, B, H_kv, N, d)) return rc;
+  if (int rc = check_strides(so, B, H, N, d)) return rc;
+  const FmStride st[4] = {to_kernel(*sq), to_kernel(*sk), to_kernel(*sv), to_kernel(*so)};
+  return fwd_impl(q, k, v, lts, lte, uts, ute, scale, out, lse, B, H, H_kv, N, d, st, workspace, workspace_bytes,
+                  hip_stream);
+}
+
+static int bwd_impl(const void* q, const void* k, const void* v, const void* out, const float* lse, const void* dout,
+                    const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute, float scale,
+                    void* dq, void* dk, void* dv, int B, int H, int Hk, int N, int d,
+                    const FmStride* st /* q, k, v, out, dout, dq, dk, dv; NULL = contiguous, Hk == H */,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!q || !k || !v || !out || !lse || !dout || !lts || !lte || !uts || !ute || !dq || !dk || !dv) return FM_ERR_NULL;
   if (int rc = check_shape(B, H, N, d)) return rc;
   if (!(scale > 0.f) || !(scale < 3.0e38f)) return FM_ERR_ARG;
@@ -198,7 +242,7 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
     ws += padded_bounds_bytes(B, N);
   }
   const PassSpace sq = pass_space(B, H, Np, FM_DQ_BR, FM_DQ_BC, true, 0);
-  const PassSpace skv = pass_space(B, H, Np, FM_DKDV_BR, FM_DKDV_BC, false, sq.total);
+  const PassSpace skv = pass_space(B, H, Np, FM_DKDV_BR, FM_DKDV_BC, false, sq.total);   // sized for H >= Hk heads
   FmBwdArgs a;
   a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
   a.lts = lts; a.lte = lte; a.uts = uts; a.ute = ute;
@@ -209,7 +253,15 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   a.dq = dq; a.dk = dk; a.dv = dv; a.scale = scale;
   a.B = B; a.H = H; a.N = N; a.Np = Np; a.d = d;
   a.slots_dq = fm_order_slots(B * H * (Np / FM_DQ_BR));
-  a.slots_dkdv = fm_order_slots(B * H * (Np / FM_DKDV_BC));
+  a.slots_dkdv = fm_order_slots(B * Hk * (Np / FM_DKDV_BC));   // a dK/dV unit is (batch row, K/V head, key block)
+  a.general = st != nullptr;
+  a.Hk = Hk;
+  if (st) {
+    a.sq = st[0]; a.sk = st[1]; a.sv = st[2]; a.so = st[3]; a.sdo = st[4]; a.sdq = st[5]; a.sdk = st[6]; a.sdv = st[7];
+  } else {
+    a.sq = a.so = a.sdo = a.sdq = dense(H, N, d);
+    a.sk = a.sv = a.sdk = a.sdv = dense(Hk, N, d);
+  }
   e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
   e = fm_launch_row_order(a.minmax_dq, B, H, Np, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.range),
@@ -217,7 +269,7 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   if (e != hipSuccess) return hip_fail(e);
   e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_DKDV_BC, (int*)(ws + skv.minmax), stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_col_order(a.minmax_dkdv, B, H, Np, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
+  e = fm_launch_col_order(a.minmax_dkdv, B, Hk, Np, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
                           (int*)(ws + skv.range), (int*)(ws + skv.order), stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
@@ -231,6 +283,31 @@ int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, 
   if (e != hipSuccess) return hip_fail(e);
   mark(4, stream);
   return FM_OK;
+}
+
+int flashmask_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse, const void* dout,
+                  const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute, float scale,
+                  void* dq, void* dk, void* dv, int B, int H, int N, int d, void* workspace, size_t workspace_bytes,
+                  void* hip_stream) {
+  return bwd_impl(q, k, v, out, lse, dout, lts, lte, uts, ute, scale, dq, dk, dv, B, H, H, N, d, nullptr, workspace,
+                  workspace_bytes, hip_stream);
+}
+
+int flashmask_bwd_ex(const void* q, const void* k, const void* v, const void* out, const float* lse, const void* dout,
+                     const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute, float scale,
+                     void* dq, void* dk, void* dv, int B, int H, int H_kv, int N, int d,
+                     const flashmask_strides* strides, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (int rc = check_shape(B, H, N, d)) return rc;
+  if (H_kv <= 0 || H % H_kv != 0) return FM_ERR_SHAPE;
+  if (!strides) return FM_ERR_NULL;
+  FmStride st[8];
+  for (int t = 0; t < 8; ++t) {
+    const bool kv = (t == 1 || t == 2 || t == 6 || t == 7);   // k, v, dk, dv have H_kv heads
+    if (int rc = check_strides(strides + t, B, kv ? H_kv : H, N, d)) return rc;
+    st[t] = to_kernel(strides[t]);
+  }
+  return bwd_impl(q, k, v, out, lse, dout, lts, lte, uts, ute, scale, dq, dk, dv, B, H, H_kv, N, d, st, workspace,
+                  workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

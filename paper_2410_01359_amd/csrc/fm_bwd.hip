@@ -20,10 +20,11 @@ namespace fm {
 // D pre-pass: writes -D_i = -sum_c dO_ic O_ic (plus the log2-domain copy of lse the tile loops use).  One row per
 // 16 (d = 128) or 8 (d = 64) lanes, 16 bytes per lane.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool GEN>
 __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                                                    const float* __restrict__ lse, float* __restrict__ dvec,
-                                                   float* __restrict__ lse2, long long slices, int n, int np) {
+                                                   float* __restrict__ lse2, long long slices, int heads, int n, int np,
+                                                   FmStride so, FmStride sdo) {
   constexpr int LPR = D / 8;  // lanes per row
   const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long prow = gid / LPR;              // row index in the padded [slices][np] layout
@@ -34,8 +35,11 @@ __global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ ou
   const long long row = bh * n + r;
   float acc = 0.f;
   if (real) {
-    const bf16x8 o = *(const bf16x8*)(out + row * D + part * 8);
-    const bf16x8 g = *(const bf16x8*)(dout + row * D + part * 8);
+    const long long b = bh / heads, h = bh - b * heads;
+    const __bf16* orow = GEN ? out + b * so.b + h * so.h + (long long)r * so.n : out + row * D;
+    const __bf16* grow = GEN ? dout + b * sdo.b + h * sdo.h + (long long)r * sdo.n : dout + row * D;
+    const bf16x8 o = *(const bf16x8*)(orow + part * 8);
+    const bf16x8 g = *(const bf16x8*)(grow + part * 8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc += (float)o[e] * (float)g[e];
   }
@@ -69,7 +73,7 @@ struct DqCfg {
 };
 
 // RAGGED: see the forward kernel -- loops at the padded length, clamped tile copies, guarded stores.
-template <int D, bool RAGGED>
+template <int D, bool RAGGED, bool GEN>
 __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   using C = DqCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
@@ -90,10 +94,13 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   const int row = qw0 + c;  // this lane's query row
   const int row_ld = RAGGED ? min(row, Nr - 1) : row;
 
-  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * Nr * D;
-  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * Nr * D;
-  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * Nr * D;
-  const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * Nr * D;
+  const int h = bh - b * H, hk = GEN ? h / (H / a.Hk) : h, Hk = GEN ? a.Hk : H;
+  const __bf16* qp = slice_ptr<D, GEN>(a.q, a.sq, b, h, H, Nr);
+  const __bf16* kp = slice_ptr<D, GEN>(a.k, a.sk, b, hk, Hk, Nr);
+  const __bf16* vp = slice_ptr<D, GEN>(a.v, a.sv, b, hk, Hk, Nr);
+  const __bf16* dop = slice_ptr<D, GEN>(a.dout, a.sdo, b, h, H, Nr);
+  const int q_rs = row_stride<D, GEN>(a.sq), k_rs = row_stride<D, GEN>(a.sk), v_rs = row_stride<D, GEN>(a.sv);
+  const int do_rs = row_stride<D, GEN>(a.sdo);
   const int* table = a.minmax_dq + (size_t)b * 8 * t_c;
   // lanes of wave 0 copy the four bound slices of a partially masked tile
   const int* my_bvec;
@@ -105,14 +112,16 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     if (which == 3) p = a.ute;
     my_bvec = p + (size_t)b * N + (lane & 15) * 4;
   }
-  CopyLanes<D> copy_lanes;
-  copy_lanes.init(lane);
+  CopyLanes<D> copy_lanes, copy_lanes_v_;
+  copy_lanes.init(lane, 2 * k_rs);
+  if (GEN) copy_lanes_v_.init(lane, 2 * v_rs);
+  const CopyLanes<D>& copy_lanes_v = GEN ? copy_lanes_v_ : copy_lanes;
 
   bf16x8 qreg[NKK], doreg[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    qreg[kk] = *(const bf16x8*)(qp + (size_t)row_ld * D + kk * 16 + 8 * g);
-    doreg[kk] = *(const bf16x8*)(dop + (size_t)row_ld * D + kk * 16 + 8 * g);
+    qreg[kk] = *(const bf16x8*)(qp + (size_t)row_ld * q_rs + kk * 16 + 8 * g);
+    doreg[kk] = *(const bf16x8*)(dop + (size_t)row_ld * do_rs + kk * 16 + 8 * g);
   }
   // lse in the log2 domain (+inf for a row with no visible key, so that P = 0 there)
   float lse2 = a.lse2[(size_t)bh * N + row];
@@ -145,11 +154,11 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
     if (RAGGED && (j_ + 1) * KT > Nr) {                                                        \
-      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane);                            \
-      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_ + C::K_BYTES, wave, lane);               \
+      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane, 2 * k_rs);                  \
+      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_ + C::K_BYTES, wave, lane, 2 * v_rs);     \
     } else {                                                                                   \
-      tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                     \
-      tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_ + C::K_BYTES, wave);        \
+      tile_load_async<D>(kp + (size_t)j_ * KT * k_rs, copy_lanes, st_, wave, 2 * k_rs);        \
+      tile_load_async<D>(vp + (size_t)j_ * KT * v_rs, copy_lanes_v, st_ + C::K_BYTES, wave, 2 * v_rs); \
     }                                                                                          \
     if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
@@ -261,7 +270,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   }
 #undef FM_LOAD_TILE
 
-  __bf16* dqp = (__bf16*)a.dq + (size_t)bh * Nr * D;
+  __bf16* dqp = (__bf16*)slice_ptr<D, GEN>(a.dq, a.sdq, b, h, H, Nr);
+  const int dq_rs = row_stride<D, GEN>(a.sdq);
   if (RAGGED && row >= Nr) return;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -270,7 +280,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
       bf16x4 o4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(dqacc[db][rq * 4 + e] * a.scale);
-      *(bf16x4*)(dqp + (size_t)row * D + db * 32 + 8 * rq + 4 * g) = o4;
+      *(bf16x4*)(dqp + (size_t)row * dq_rs + db * 32 + 8 * rq + 4 * g) = o4;
     }
 }
 
@@ -354,13 +364,15 @@ __device__ __forceinline__ void dkdv_stage_a(const f32x16& s, const f32x16& dp, 
 struct DkdvAhead {
   const char* nqs;        // LDS: stage of the next list entry (its Q tile; dO follows), for the operand prefetch
   int v_copy;             // list entry (still in a vector register) of the tile NSTAGE - 1 ahead, to be copied
-  const char* q_base;     // global Q / dO of this (batch, head) and this lane's lse2 / D source
-  const char* do_base;
+  const char* q_base;     // global Q / dO of this (batch, head), already advanced to this wave's 16-row block
+  const char* do_base;    // of a tile, and this lane's lse2 / D source
   const float* vec_src;
+  int q_rs2, do_rs2;      // bytes between consecutive rows of Q / dO in global memory
   unsigned lds_ring;      // LDS address of stage 0
   unsigned stage_copy;    // index of the stage that receives the copy
   int n_real, lane;       // ragged sequences: rows the tensors really have, and this thread's lane
-  CopyLanes<128> lanes;   // per-lane source offsets of the copy instructions (the first D/32 entries are used)
+  CopyLanes<128> lanes;   // per-lane source offsets of the copy instructions of Q (the first D/32 entries are used)
+  CopyLanes<128> lanes_do;   // ... and of dO
   int wave;
 };
 
@@ -377,16 +389,17 @@ __device__ __forceinline__ void dkdv_issue_copy(const DkdvAhead& ah, const char*
     const int row = ah.wave * 16 + S * RPI + ah.lane / C::L::CPR;
     const int grow = min(i_copy * C::QT + row, ah.n_real - 1);
     const char* base = K < HALF ? ah.q_base : ah.do_base;
-    const char* src = base + (size_t)grow * C::L::RS + (((ah.lane % C::L::CPR) ^ C::L::swz(row)) << 4);
+    const long long rel = (long long)(grow - ah.wave * 16) * (K < HALF ? ah.q_rs2 : ah.do_rs2);   // the bases are this wave's
+    const char* src = base + rel + (((ah.lane % C::L::CPR) ^ C::L::swz(row)) << 4);
     async_copy16(src, lds_stage + (K < HALF ? 0 : C::Q_BYTES) + ah.wave * WB + S * 1024);
     return;
   }
   if (K < HALF) {
     if (K == 0 || RAGGED) async_window(lds_stage + ah.wave * WB);
-    async_copy16_window<(K % HALF) * 1024>(q_src + ah.wave * WB, ah.lanes.v[K % HALF]);
+    async_copy16_window<(K % HALF) * 1024>(q_src, ah.lanes.v[K % HALF]);
   } else if (K < C::COPIES) {
     if (K == HALF || RAGGED) async_window(lds_stage + C::Q_BYTES + ah.wave * WB);
-    async_copy16_window<(K % HALF) * 1024>(do_src + ah.wave * WB, ah.lanes.v[K % HALF]);
+    async_copy16_window<(K % HALF) * 1024>(do_src, ah.lanes_do.v[K % HALF]);
   } else {
     async_copy16_lanes8(vec_src, lds_stage + C::Q_BYTES + C::DO_BYTES + ah.wave * 128);
   }
@@ -506,8 +519,8 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
     if (x == XS) {
       dkdv_sync<D>();
       i_copy = __builtin_amdgcn_readfirstlane(ah.v_copy) & 0xFFFFFF;
-      q_src = ah.q_base + (size_t)i_copy * (C::QT * D * 2);
-      do_src = ah.do_base + (size_t)i_copy * (C::QT * D * 2);
+      q_src = ah.q_base + (size_t)i_copy * C::QT * ah.q_rs2;
+      do_src = ah.do_base + (size_t)i_copy * C::QT * ah.do_rs2;
       vec_src = ah.vec_src + i_copy * C::QT;
       lds_stage = ah.lds_ring + ah.stage_copy * C::STAGE;
     }
@@ -565,7 +578,10 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
 
 // RAGGED: see the forward kernel -- loops at the padded length, clamped tile copies and fragment
 // loads, guarded stores; the padding rows carry lse = +inf (P = 0), the padding keys are masked.
-template <int D, bool RAGGED>
+// GEN: tensors with caller-given strides; a workgroup then owns 128 keys of one K/V head and
+// walks the query heads that share it one after the other (same list of live row blocks: the
+// mask does not depend on the head), accumulating dK and dV over all of them.
+template <int D, bool RAGGED, bool GEN>
 __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   using C = DkdvCfg<D>;
   constexpr int QT = C::QT, NDB = D / 32, NKK = D / 16;
@@ -579,20 +595,19 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, c = lane & 31;
   const int N = a.Np, H = a.H;            // padded length: what the loops and tables see
+  const int Hk = GEN ? a.Hk : H, G = GEN ? H / Hk : 1;   // K/V heads, query heads per K/V head
   const int Nr = RAGGED ? a.N : a.Np;     // rows the tensors really have
   const int t_r = N / QT, t_c = N / C::BC;
-  const int bh = unit / t_c, j_blk = unit - bh * t_c, b = bh / H;
+  const int bh = unit / t_c, j_blk = unit - bh * t_c, b = bh / Hk, hk = bh - b * Hk;   // bh counts K/V heads
   const int k0 = j_blk * C::BC;
   const int kw0 = k0 + wave * 32;
   const int key = kw0 + c;  // this lane's key column
   const int key_ld = RAGGED ? min(key, Nr - 1) : key;
 
-  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * Nr * D;
-  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * Nr * D;
-  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * Nr * D;
-  const __bf16* dop = (const __bf16*)a.dout + (size_t)bh * Nr * D;
-  const float* lsep = a.lse2 + (size_t)bh * N;
-  const float* dvp = a.dvec + (size_t)bh * N;
+  const __bf16* kp = slice_ptr<D, GEN>(a.k, a.sk, b, hk, Hk, Nr);
+  const __bf16* vp = slice_ptr<D, GEN>(a.v, a.sv, b, hk, Hk, Nr);
+  const int q_rs = row_stride<D, GEN>(a.sq), k_rs = row_stride<D, GEN>(a.sk), v_rs = row_stride<D, GEN>(a.sv);
+  const int do_rs = row_stride<D, GEN>(a.sdo);
 
   // What the list of live row blocks needs comes first, so that its latency is not queued
   // behind the fragment loads below: the block's min/max values.
@@ -604,8 +619,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   bf16x8 kreg[NKK], vreg[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    kreg[kk] = *(const bf16x8*)(kp + (size_t)key_ld * D + kk * 16 + 8 * g);
-    vreg[kk] = *(const bf16x8*)(vp + (size_t)key_ld * D + kk * 16 + 8 * g);
+    kreg[kk] = *(const bf16x8*)(kp + (size_t)key_ld * k_rs + kk * 16 + 8 * g);
+    vreg[kk] = *(const bf16x8*)(vp + (size_t)key_ld * v_rs + kk * 16 + 8 * g);
   }
   int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
   int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
@@ -627,20 +642,21 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const int a_base = C::L::off(c, 16 * g);
   const int t_base0 = C::L::off(4 * g + (i16 >> 2), (16 * half + 4 * (i16 & 3)) * 2);
   const int t_base1 = C::L::off(4 * g + (i16 >> 2) + 8, (16 * half + 4 * (i16 & 3)) * 2);
-  CopyLanes<D> copy_lanes;
-  copy_lanes.init(lane);
-  // every wave copies its 16 rows of the tile's lse and D slices with lanes 0..7:
-  // lanes 0-3 lse, lanes 4-7 D, 16 bytes each
-  const float* my_vec = ((lane & 4) ? dvp : lsep) + wave * 16 + (lane & 3) * 4;
+  CopyLanes<D> copy_lanes, copy_lanes_do_;
+  copy_lanes.init(lane, 2 * q_rs);
+  if (GEN) copy_lanes_do_.init(lane, 2 * do_rs);
+  const CopyLanes<D>& copy_lanes_do = GEN ? copy_lanes_do_ : copy_lanes;
   const unsigned lds_ring = lds_address(smem + C::STAGE_OFF);
 
   DkdvAhead ah;
-  ah.q_base = (const char*)qp;
-  ah.do_base = (const char*)dop;
-  ah.vec_src = my_vec;
+  ah.q_rs2 = 2 * q_rs;
+  ah.do_rs2 = 2 * do_rs;
   ah.lds_ring = lds_ring;
 #pragma unroll
-  for (int s = 0; s < CopyLanes<D>::NINST; ++s) ah.lanes.v[s] = copy_lanes.v[s];
+  for (int s = 0; s < CopyLanes<D>::NINST; ++s) {
+    ah.lanes.v[s] = copy_lanes.v[s];
+    ah.lanes_do.v[s] = copy_lanes_do.v[s];
+  }
   ah.wave = wave;
   ah.n_real = Nr;
   ah.lane = lane;
@@ -671,17 +687,28 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     int n_plain = 0;
     const int n_live = build_live_row_blocks(gmm, N, QT, chunk, min(chunk + C::LIST_CAP, i_hi), list, wave_cnt, n_plain);
     if (n_live == 0) continue;
+    // the query heads that share this K/V head, one after the other (one pass if there is no sharing)
+    for (int hq = 0; hq < (GEN ? G : 1); ++hq) {
+    const int h = hk * G + hq;
+    const __bf16* qp = slice_ptr<D, GEN>(a.q, a.sq, b, h, H, Nr);
+    const __bf16* dop = slice_ptr<D, GEN>(a.dout, a.sdo, b, h, H, Nr);
+    // every wave copies its 16 rows of a tile's lse and D slices with lanes 0..7:
+    // lanes 0-3 lse, lanes 4-7 D, 16 bytes each
+    const float* my_vec = ((lane & 4) ? a.dvec : a.lse2) + (size_t)(b * H + h) * N + wave * 16 + (lane & 3) * 4;
+    ah.q_base = (const char*)qp + (size_t)(wave * 16) * ah.q_rs2;
+    ah.do_base = (const char*)dop + (size_t)(wave * 16) * ah.do_rs2;
+    ah.vec_src = my_vec;
     // prologue: copies of the first NSTAGE - 1 tiles, then the first tile's first operands
 #pragma unroll
     for (int p = 0; p < C::NSTAGE - 1; ++p) {
       const int i_p = __builtin_amdgcn_readfirstlane(list[min(p, n_live - 1)]) & 0xFFFFFF;
       char* st_ = smem + C::STAGE_OFF + p * C::STAGE;
       if (RAGGED && (i_p + 1) * QT > Nr) {
-        tile_load_async_clamped<D>(qp, i_p * QT, Nr, st_, wave, lane);
-        tile_load_async_clamped<D>(dop, i_p * QT, Nr, st_ + C::Q_BYTES, wave, lane);
+        tile_load_async_clamped<D>(qp, i_p * QT, Nr, st_, wave, lane, 2 * q_rs);
+        tile_load_async_clamped<D>(dop, i_p * QT, Nr, st_ + C::Q_BYTES, wave, lane, 2 * do_rs);
       } else {
-        tile_load_async<D>(qp + (size_t)i_p * QT * D, copy_lanes, st_, wave);
-        tile_load_async<D>(dop + (size_t)i_p * QT * D, copy_lanes, st_ + C::Q_BYTES, wave);
+        tile_load_async<D>(qp + (size_t)i_p * QT * q_rs, copy_lanes, st_, wave, 2 * q_rs);
+        tile_load_async<D>(dop + (size_t)i_p * QT * do_rs, copy_lanes_do, st_ + C::Q_BYTES, wave, 2 * do_rs);
       }
       async_copy16_lanes8(my_vec + i_p * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES) + wave * 128);
     }
@@ -705,21 +732,23 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     FM_TILE_LOOP(0, n_plain, false)
     FM_TILE_LOOP(n_plain, n_live, true)
     async_wait<0>();   // the copies made for entries past the end must not outlive the list / the workgroup
-    __syncthreads();   // the list and the ring are rebuilt by the next chunk
+    __syncthreads();   // the ring is refilled by the next head, the list rebuilt by the next chunk
+    }  // query heads
   }
 #undef FM_TILE_LOOP
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
-  __bf16* dkp = (__bf16*)a.dk + (size_t)bh * Nr * D;
-  __bf16* dvp_out = (__bf16*)a.dv + (size_t)bh * Nr * D;
+  __bf16* dkp = (__bf16*)slice_ptr<D, GEN>(a.dk, a.sdk, b, hk, Hk, Nr);
+  __bf16* dvp_out = (__bf16*)slice_ptr<D, GEN>(a.dv, a.sdv, b, hk, Hk, Nr);
+  const int dk_rs = row_stride<D, GEN>(a.sdk), dv_rs = row_stride<D, GEN>(a.sdv);
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int krow = kw0 + 8 * (r >> 2) + 4 * g + (r & 3);
       if (RAGGED && krow >= Nr) continue;
-      dkp[(size_t)krow * D + db * 32 + c] = (__bf16)(dkacc[db][r] * a.scale);
-      dvp_out[(size_t)krow * D + db * 32 + c] = (__bf16)dvacc[db][r];
+      dkp[(size_t)krow * dk_rs + db * 32 + c] = (__bf16)(dkacc[db][r] * a.scale);
+      dvp_out[(size_t)krow * dv_rs + db * 32 + c] = (__bf16)dvacc[db][r];
     }
 }
 
@@ -727,55 +756,68 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
 
 using namespace fm;
 
-hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream) {
+template <int D, bool GEN>
+static hipError_t launch_dvec_t(const FmBwdArgs& a, hipStream_t stream) {
   const long long slices = (long long)a.B * a.H;
-  const long long threads = slices * a.Np * (a.d / 8);
+  const long long threads = slices * a.Np * (D / 8);
   const unsigned blocks = (unsigned)((threads + 255) / 256);
-  if (a.d == 128)
-    hipLaunchKernelGGL(dvec_kernel<128>, dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, slices, a.N, a.Np);
-  else
-    hipLaunchKernelGGL(dvec_kernel<64>, dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                       (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, slices, a.N, a.Np);
+  hipLaunchKernelGGL((dvec_kernel<D, GEN>), dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
+                     (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, slices, a.H, a.N, a.Np, a.so, a.sdo);
   return hipGetLastError();
 }
 
-template <int D, bool RAGGED>
+hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream) {
+  if (a.d == 128) return a.general ? launch_dvec_t<128, true>(a, stream) : launch_dvec_t<128, false>(a, stream);
+  return a.general ? launch_dvec_t<64, true>(a, stream) : launch_dvec_t<64, false>(a, stream);
+}
+
+template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DqCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)dq_kernel<D, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)dq_kernel<D, RAGGED, GEN>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dq_kernel<D, RAGGED>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((dq_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
-hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream) {
+template <int D>
+static hipError_t launch_dq_d(const FmBwdArgs& a, hipStream_t stream) {
   const bool ragged = a.Np != a.N;
-  if (a.d == 128) return ragged ? launch_dq_t<128, true>(a, stream) : launch_dq_t<128, false>(a, stream);
-  return ragged ? launch_dq_t<64, true>(a, stream) : launch_dq_t<64, false>(a, stream);
+  if (a.general) return ragged ? launch_dq_t<D, true, true>(a, stream) : launch_dq_t<D, false, true>(a, stream);
+  return ragged ? launch_dq_t<D, true, false>(a, stream) : launch_dq_t<D, false, false>(a, stream);
 }
 
-template <int D, bool RAGGED>
+hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream) {
+  return a.d == 128 ? launch_dq_d<128>(a, stream) : launch_dq_d<64>(a, stream);
+}
+
+template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DkdvCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)dkdv_kernel<D, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)dkdv_kernel<D, RAGGED, GEN>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED>), dim3(fm_launch_grid(a.slots_dkdv)), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dkdv)), dim3(256), C::LDS_BYTES, stream,
+                     a);
   return hipGetLastError();
 }
 
-hipError_t fm_launch_bwd_dkdv(const FmBwdArgs& a, hipStream_t stream) {
+template <int D>
+static hipError_t launch_dkdv_d(const FmBwdArgs& a, hipStream_t stream) {
   const bool ragged = a.Np != a.N;
-  if (a.d == 128) return ragged ? launch_dkdv_t<128, true>(a, stream) : launch_dkdv_t<128, false>(a, stream);
-  return ragged ? launch_dkdv_t<64, true>(a, stream) : launch_dkdv_t<64, false>(a, stream);
+  if (a.general) return ragged ? launch_dkdv_t<D, true, true>(a, stream) : launch_dkdv_t<D, false, true>(a, stream);
+  return ragged ? launch_dkdv_t<D, true, false>(a, stream) : launch_dkdv_t<D, false, false>(a, stream);
+}
+
+hipError_t fm_launch_bwd_dkdv(const FmBwdArgs& a, hipStream_t stream) {
+  return a.d == 128 ? launch_dkdv_d<128>(a, stream) : launch_dkdv_d<64>(a, stream);
 }

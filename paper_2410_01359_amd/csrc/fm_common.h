@@ -131,11 +131,14 @@ struct CopyLanes {
   static constexpr int RPI = 64 / L::CPR;     // rows per instruction
   static constexpr int NINST = 16 / RPI;      // instructions per wave and tile
   unsigned v[NINST];
-  __device__ __forceinline__ void init(int lane) {
+  // grs: bytes between consecutive rows of the global tensor (TileLayout::RS when it is
+  // contiguous).  Instruction s carries the immediate s * 1024 on both sides, so what its rows
+  // are really apart in global memory beyond that goes into the lane offset.
+  __device__ __forceinline__ void init(int lane, int grs = L::RS) {
 #pragma unroll
     for (int s = 0; s < NINST; ++s) {
       const int row = lane / L::CPR;          // row within the instruction's 1 KB
-      v[s] = row * L::RS + (((lane % L::CPR) ^ L::swz(s * RPI + row)) << 4);
+      v[s] = (s * RPI + row) * grs - s * 1024 + (((lane % L::CPR) ^ L::swz(s * RPI + row)) << 4);
     }
   }
 };
@@ -212,8 +215,8 @@ __device__ __forceinline__ void tile_copy_inst(const void* wave_src, const CopyL
 // A wave's whole part of a [64][D] tile copy: tile_src / lds_tile are the tile's first row.
 template <int D>
 __device__ __forceinline__ void tile_load_async(const __bf16* tile_src, const CopyLanes<D>& cl, const char* lds_tile,
-                                                int wave) {
-  const char* wave_src = (const char*)tile_src + wave * 16 * TileLayout<D>::RS;
+                                                int wave, int grs = TileLayout<D>::RS) {
+  const char* wave_src = (const char*)tile_src + (size_t)(wave * 16) * grs;
   async_window(lds_address(lds_tile) + wave * 16 * TileLayout<D>::RS);
   tile_copy_inst<D, 0>(wave_src, cl);
   tile_copy_inst<D, 1>(wave_src, cl);
@@ -229,16 +232,30 @@ __device__ __forceinline__ void tile_load_async(const __bf16* tile_src, const Co
 // result.  tensor_bh is row 0 of the (batch, head) slice, row0 the tile's first row.
 template <int D>
 __device__ __forceinline__ void tile_load_async_clamped(const __bf16* tensor_bh, int row0, int n_real,
-                                                        const char* lds_tile, int wave, int lane) {
+                                                        const char* lds_tile, int wave, int lane,
+                                                        int grs = TileLayout<D>::RS) {
   using L = TileLayout<D>;
   constexpr int RPI = 64 / L::CPR, NINST = 16 / RPI;
 #pragma unroll
   for (int s = 0; s < NINST; ++s) {
     const int row = wave * 16 + s * RPI + lane / L::CPR;
     const int grow = min(row0 + row, n_real - 1);
-    const char* src = (const char*)tensor_bh + (size_t)grow * L::RS + (((lane % L::CPR) ^ L::swz(row)) << 4);
+    const char* src = (const char*)tensor_bh + (size_t)grow * grs + (((lane % L::CPR) ^ L::swz(row)) << 4);
     async_copy16(src, lds_address(lds_tile) + wave * 16 * L::RS + s * 1024);
   }
+}
+
+// Where a (batch, head) slice of a tensor starts and how far its rows are apart, in elements:
+// taken from the stride record in the general instantiations, compile-time otherwise.
+template <int D, bool GEN>
+__device__ __forceinline__ const __bf16* slice_ptr(const void* base, const FmStride& st, int b, int h, int heads,
+                                                   int n_rows) {
+  if (GEN) return (const __bf16*)base + (size_t)b * st.b + (size_t)h * st.h;
+  return (const __bf16*)base + (size_t)(b * heads + h) * n_rows * D;
+}
+template <int D, bool GEN>
+__device__ __forceinline__ int row_stride(const FmStride& st) {
+  return GEN ? (int)st.n : D;
 }
 
 // Force a value that was fetched with an ordinary global load to be complete

@@ -167,7 +167,8 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
 // Np (tables, lists and the padded bound vectors are built for it; the padding columns are masked
 // for every row), tile copies that reach past row N clamp their source rows, and rows >= N are
 // computed but not stored.
-template <int D, bool RAGGED>
+// GEN: tensors with caller-given strides and fewer K/V heads than query heads (see FmFwdArgs).
+template <int D, bool RAGGED, bool GEN>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   using C = FwdCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16, QB = 1;
@@ -186,9 +187,11 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   const int q0 = i_blk * C::BR;
   const int qw0 = q0 + wave * 32;
 
-  const __bf16* qp = (const __bf16*)a.q + (size_t)bh * Nr * D;
-  const __bf16* kp = (const __bf16*)a.k + (size_t)bh * Nr * D;
-  const __bf16* vp = (const __bf16*)a.v + (size_t)bh * Nr * D;
+  const int h = bh - b * H, hk = GEN ? h / (H / a.Hk) : h, Hk = GEN ? a.Hk : H;
+  const __bf16* qp = slice_ptr<D, GEN>(a.q, a.sq, b, h, H, Nr);
+  const __bf16* kp = slice_ptr<D, GEN>(a.k, a.sk, b, hk, Hk, Nr);
+  const __bf16* vp = slice_ptr<D, GEN>(a.v, a.sv, b, hk, Hk, Nr);
+  const int q_rs = row_stride<D, GEN>(a.sq), k_rs = row_stride<D, GEN>(a.sk), v_rs = row_stride<D, GEN>(a.sv);
   const int* table = a.minmax + (size_t)b * 8 * t_c;
   // lanes of wave 0 copy the four bound slices of a partially masked tile: lane l moves
   // 16 bytes of vector l / 16
@@ -201,14 +204,16 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
     if (which == 3) p = a.ute;
     my_bvec = p + (size_t)b * N + (lane & 15) * 4;
   }
-  CopyLanes<D> copy_lanes;
-  copy_lanes.init(lane);
+  CopyLanes<D> copy_lanes, copy_lanes_v_;
+  copy_lanes.init(lane, 2 * k_rs);
+  if (GEN) copy_lanes_v_.init(lane, 2 * v_rs);
+  const CopyLanes<D>& copy_lanes_v = GEN ? copy_lanes_v_ : copy_lanes;
 
   // Q fragments (B operand of S^T = K Q^T): lane holds Q[row c][16 kk + 8 g ..+7].
   bf16x8 qreg[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk)
-    qreg[kk] = *(const bf16x8*)(qp + (size_t)(RAGGED ? min(qw0 + c, Nr - 1) : qw0 + c) * D + kk * 16 + 8 * g);
+    qreg[kk] = *(const bf16x8*)(qp + (size_t)(RAGGED ? min(qw0 + c, Nr - 1) : qw0 + c) * q_rs + kk * 16 + 8 * g);
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) settle(qreg[kk]);
 
@@ -239,18 +244,18 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
     const int j_ = entry_block(ENTRY, chunk);                                                    \
     char* st_ = smem + C::K_OFF + (KBUF) * C::K_BYTES;                                           \
     if (RAGGED && (j_ + 1) * KT > Nr)                                                            \
-      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane);                              \
+      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane, 2 * k_rs);                    \
     else                                                                                         \
-      tile_load_async<D>(kp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                       \
+      tile_load_async<D>(kp + (size_t)j_ * KT * k_rs, copy_lanes, st_, wave, 2 * k_rs);          \
   }
 #define FM_LOAD_V(ENTRY, VBUF)                                                                   \
   {                                                                                              \
     const int j_ = entry_block(ENTRY, chunk);                                                    \
     char* st_ = smem + C::V_OFF + (VBUF) * C::VSTAGE;                                            \
     if (RAGGED && (j_ + 1) * KT > Nr)                                                            \
-      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_, wave, lane);                              \
+      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_, wave, lane, 2 * v_rs);                    \
     else                                                                                         \
-      tile_load_async<D>(vp + (size_t)j_ * KT * D, copy_lanes, st_, wave);                       \
+      tile_load_async<D>(vp + (size_t)j_ * KT * v_rs, copy_lanes_v, st_, wave, 2 * v_rs);        \
     if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                       \
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::V_BYTES));                            \
   }
@@ -310,7 +315,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
 #undef FM_LOAD_V
 
   // epilogue: O / l, lse = m + log(l)   (m, l in the log2 domain)
-  __bf16* op = (__bf16*)a.out + (size_t)bh * Nr * D;
+  __bf16* op = (__bf16*)slice_ptr<D, GEN>(a.out, a.so, b, h, H, Nr);
+  const int o_rs = row_stride<D, GEN>(a.so);
   float* lp = a.lse + (size_t)bh * Nr;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -325,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
           bf16x4 o4;
 #pragma unroll
           for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][rq * 4 + e] * inv);
-          *(bf16x4*)(op + (size_t)row * D + db * 32 + 8 * rq + 4 * g) = o4;
+          *(bf16x4*)(op + (size_t)row * o_rs + db * 32 + 8 * rq + 4 * g) = o4;
         }
       if (g == 0) lp[row] = lt > 0.f ? (m_run + fast_log2(lt)) * kLn2 : -INFINITY;
     }
@@ -336,23 +342,28 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
 
 using namespace fm;
 
-template <int D, bool RAGGED>
+template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_fwd_t(const FmFwdArgs& a, hipStream_t stream) {
   using C = FwdCfg<D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D, RAGGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D, RAGGED, GEN>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fwd_kernel<D, RAGGED>), dim3(fm_launch_grid(a.slots)), dim3(256), C::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((fwd_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_fwd_d(const FmFwdArgs& a, hipStream_t stream) {
+  const bool ragged = a.Np != a.N;
+  if (a.general) return ragged ? launch_fwd_t<D, true, true>(a, stream) : launch_fwd_t<D, false, true>(a, stream);
+  return ragged ? launch_fwd_t<D, true, false>(a, stream) : launch_fwd_t<D, false, false>(a, stream);
 }
 
 hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream) {
   static_assert(FM_FWD_BR == 128, "forward row block");
-  const bool ragged = a.Np != a.N;
-  if (a.d == 128) return ragged ? launch_fwd_t<128, true>(a, stream) : launch_fwd_t<128, false>(a, stream);
-  return ragged ? launch_fwd_t<64, true>(a, stream) : launch_fwd_t<64, false>(a, stream);
+  return a.d == 128 ? launch_fwd_d<128>(a, stream) : launch_fwd_d<64>(a, stream);
 }

@@ -38,6 +38,14 @@ hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block
 hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream);
 
+// Element strides of a bf16 tensor indexed [batch][head][row][d] (d contiguous).
+struct FmStride {
+  long long b, h, n;
+};
+
+// `general` selects the kernel instantiations that honour the stride fields and Hk (number of
+// K/V heads, H % Hk == 0: query head h reads K/V head h / (H / Hk)); otherwise every tensor is
+// contiguous [B,H,N,d], Hk == H, and the strides are compile-time constants of the kernels.
 // N is the true sequence length (stride of the tensors), Np = N rounded up to a multiple of 128: the
 // length the tile loops and the tables work at.  When Np > N the bound vectors are the library's
 // padded copies [B][Np] whose extra columns are masked for every row.
@@ -52,6 +60,9 @@ struct FmFwdArgs {
   float scale;
   int B, H, N, Np, d;
   int slots;
+  bool general;
+  int Hk;
+  FmStride sq, sk, sv, so;
 };
 hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream);
 
@@ -69,6 +80,9 @@ struct FmBwdArgs {
   float scale;
   int B, H, N, Np, d;
   int slots_dq, slots_dkdv;
+  bool general;
+  int Hk;
+  FmStride sq, sk, sv, so, sdo, sdq, sdk, sdv;
 };
 hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream);
 hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream);
