@@ -191,17 +191,15 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
         for (int kb = 0; kb < NKB; ++kb) {
           f32x16 sacc, dpacc;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            sacc[r] = 0.f;
-            dpacc[r] = 0.f;
-          }
-          // S^T = K Q^T and dP^T = V dO^T for 32 keys x 32 queries: 2*NKK MFMA steps, S and dP
-          // alternating (two accumulation chains); the LDS operand of a step is fetched RS steps
-          // ahead into a small register ring.
-          constexpr int NS = 2 * NKK, RS = 4, NT = 2 * NDB, RT = 3;
+          for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+          // S^T = K Q^T, then dP^T = V dO^T, for 32 keys x 32 queries: 2*NKK MFMA steps; the LDS
+          // operand of a step is fetched RS steps ahead into a small register ring.  The S chain
+          // goes first, so that the exponentials P = exp(S - L) can ride along with the dP chain.
+          constexpr int NS = 2 * NKK, RS = 3, NT = 2 * NDB, RT = 3;
+          constexpr int EXPS = (16 + NKK - 2) / (NKK - 1);   // exponentials next to each of the last NKK - 1 dP steps
           auto s_operand = [&](int n) __attribute__((always_inline)) {
-            const char* tile = (n & 1) ? vs : ks;
-            return *(const bf16x8*)(tile + kb * 32 * C::L::RS + C::L::add_col(a_b, (n / 2) * 32));
+            const char* tile = (n >= NKK) ? vs : ks;
+            return *(const bf16x8*)(tile + kb * 32 * C::L::RS + C::L::add_col(a_b, (n % NKK) * 32));
           };
           auto t_operand = [&](int n) __attribute__((always_inline)) {
             const char* krow = ks + (kb * 32 + 16 * (n / NDB)) * C::L::RS;
@@ -213,19 +211,18 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
           for (int n = 0; n < RS; ++n) ring[n] = s_operand(n);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int n = 0; n < NS; ++n) {
-            if (n & 1)
-              dpacc = mfma32(ring[n % RS], doreg[n / 2], dpacc);
-            else
-              sacc = mfma32(ring[n % RS], qreg[n / 2], sacc);
+          for (int n = 0; n <= NKK; ++n) {   // the S chain and the first dP step
+            if (n < NKK) {
+              sacc = mfma32(ring[n % RS], qreg[n], sacc);
+            } else {
+              // the dP accumulator starts from -D of this lane's row, so it ends as dP - D
+#pragma unroll
+              for (int r = 0; r < 16; ++r) dpacc[r] = dneg;
+              dpacc = mfma32(ring[n % RS], doreg[0], dpacc);
+            }
             if (n + RS < NS) ring[n % RS] = s_operand(n + RS);
             __builtin_amdgcn_sched_barrier(0);
           }
-          // K^T operands of the dQ product do not depend on dS: fetch the first ones now
-          bf16x8 tring[RT];
-#pragma unroll
-          for (int n = 0; n < RT; ++n) tring[n] = t_operand(n);
-          __builtin_amdgcn_sched_barrier(0);
           if (wcls & T_PARTIAL) {
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
@@ -240,13 +237,29 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
                 if (masked) sacc[rq * 4 + e] = -INFINITY;
               }
             }
+            __builtin_amdgcn_sched_barrier(0);
           }
-          // P = exp(S - L), dS = P o (dP - D)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(__builtin_fmaf(sacc[r], sc, -lse2));
-            sacc[r] = p * (dpacc[r] + dneg);
+          for (int n = NKK + 1; n < NS; ++n) {   // the rest of the dP chain, P = exp(S - L) beside it
+            dpacc = mfma32(ring[n % RS], doreg[n - NKK], dpacc);
+            if (n + RS < NS) ring[n % RS] = s_operand(n + RS);
+#pragma unroll
+            for (int r = (n - NKK - 1) * EXPS; r < (n - NKK) * EXPS && r < 16; ++r)
+              sacc[r] = fast_exp2(__builtin_fmaf(sacc[r], sc, -lse2));
+            __builtin_amdgcn_sched_barrier(0);
           }
+          // K^T operands of the dQ product do not depend on dS: fetch the first ones now
+          bf16x8 tring[RT];
+#pragma unroll
+          for (int n = 0; n < RT; ++n) tring[n] = t_operand(n);
+          __builtin_amdgcn_sched_barrier(0);
+          // dS = P o (dP - D): the first 16-key half before the dQ product, the second half spread
+          // over the product's first NDB steps (which only need the first)
+          auto ds_elems = [&](int r0, int r1) __attribute__((always_inline)) {
+#pragma unroll
+            for (int r = r0; r < r1; ++r) sacc[r] *= dpacc[r];
+          };
+          ds_elems(0, 8);
           __builtin_amdgcn_sched_barrier(0);
           // dQ^T += K^T dS^T, step n = (16-key half n / NDB, d block n % NDB)
           bf16x8 dsb;
@@ -258,6 +271,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
             }
             dqacc[n % NDB] = mfma32(tring[n % RT], dsb, dqacc[n % NDB]);
             if (n + RT < NT) tring[n % RT] = t_operand(n + RT);
+            if (n < NDB) ds_elems(8 + n * (8 / NDB), 8 + (n + 1) * (8 / NDB));
             __builtin_amdgcn_sched_barrier(0);
           }
         }
