@@ -127,3 +127,72 @@ def test_grouped_heads_in_bnhd_layout_inference_shape():
             ref_dk, ref_dv = ref_dk + rdk, ref_dv + rdv
         check_bwd(bf16_to_np(dk[0, hk]), ref_dk, "dk", f"hk={hk}")
         check_bwd(bf16_to_np(dv[0, hk]), ref_dv, "dv", f"hk={hk}")
+
+
+def test_grouped_heads_bnhd_long_sequence_closed_form():
+    """Q = 0 under a causal mask: lse_i = log(i + 1), out_i = prefix mean of V, dK = 0 and dV a
+    suffix sum (summed over the query heads of a group) -- checked on every row at a ragged length
+    whose live lists are rebuilt (more key blocks than one list holds), stored [B,N,H,d]."""
+    import paper_2410_01359_amd as fm
+    from gpu_util import ABS_BWD, ABS_FWD
+    B, H, Hk, N, d = 1, 4, 2, 70001, 128
+    G = H // Hk
+    rng = np.random.Generator(np.random.PCG64(5150))
+    kv = rng.standard_normal((2, B, Hk, N, d), dtype=np.float32)
+    do32 = rng.standard_normal((B, H, N, d), dtype=np.float32)
+    to_dev = lambda x: _bnhd(_dev(workloads.to_bf16_bits(x)))
+    rounded = lambda x: workloads.bf16_bits_to_f32(workloads.to_bf16_bits(x)).astype(np.float64)
+    q = _bnhd(torch.zeros((B, H, N, d), dtype=torch.bfloat16, device="cuda"))
+    k, v, do = to_dev(kv[0]), to_dev(kv[1]), to_dev(do32)
+    vecs = tuple(torch.from_numpy(x[None].astype(np.int32)).cuda() for x in workloads.causal_mask(N))
+    scale = 1.0 / np.sqrt(d)
+    out, lse = fm.flashmask_fwd_ex(q, k, v, *vecs, scale)
+    dq, dk, dv = fm.flashmask_bwd_ex(q, k, v, out, lse, do, *vecs, scale)
+    torch.cuda.synchronize()
+    c = np.arange(1, N + 1, dtype=np.float64)
+    vr, dor = rounded(kv[1]), rounded(do32)
+    for h in range(H):
+        assert np.abs(lse[0, h].cpu().numpy() - np.log(c)).max() <= ABS_FWD
+        assert np.abs(bf16_to_np(out[0, h]) - np.cumsum(vr[0, h // G], axis=0) / c[:, None]).max() <= ABS_FWD
+    assert torch.count_nonzero(dk.float()) == 0
+    for hk in range(Hk):
+        ref = sum(np.cumsum((dor[0, h] / c[:, None])[::-1], axis=0)[::-1] for h in range(hk * G, (hk + 1) * G))
+        assert np.abs(bf16_to_np(dv[0, hk]) - ref).max() <= ABS_BWD
+
+
+def test_forward_backward_inside_a_hip_graph():
+    """The whole path (preprocessing, unit queues, tile loops) captured into a HIP graph and
+    replayed with new inputs: every replay is bit-identical to the eager call on the same
+    inputs (the library allocates nothing and its only global-memory clears are kernels)."""
+    import paper_2410_01359_amd as fm
+    B, H, Hk, N, d = 2, 4, 2, 1000, 128
+    w, bits, vecs = _inputs("shared_question", B, H, Hk, N, d, seed=613)
+    t = {n: _dev(bits[n]) for n in bits}
+    ws_f = torch.empty(fm.flashmask_workspace_bytes(fm.FM_PASS_FWD, B, H, N, d), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(fm.flashmask_workspace_bytes(fm.FM_PASS_BWD, B, H, N, d), dtype=torch.uint8, device="cuda")
+
+    def run():
+        out, lse = fm.flashmask_fwd_ex(t["q"], t["k"], t["v"], *vecs, w.scale, workspace=ws_f)
+        return (out, lse) + tuple(fm.flashmask_bwd_ex(t["q"], t["k"], t["v"], out, lse, t["dout"], *vecs, w.scale,
+                                                      workspace=ws_b))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                  # warm-up outside the capture (kernel attributes are set on first use)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        captured = run()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    for replay in range(3):
+        for n in ("q", "dout"):                # new values in the captured buffers
+            t[n].copy_(torch.randn(t[n].shape, device="cuda", generator=gen).bfloat16())
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = run()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("out", "lse", "dq", "dk", "dv"), captured, eager):
+            assert torch.equal(a, b), f"replay {replay}: {name} differs from the eager call"
