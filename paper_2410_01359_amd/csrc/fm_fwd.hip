@@ -21,6 +21,10 @@
 
 namespace fm {
 
+#ifndef FM_FWD_EXP_A
+#define FM_FWD_EXP_A 20
+#endif
+
 template <int D>
 struct FwdCfg {
   static constexpr int KT = FM_FWD_BC;          // keys per tile
@@ -92,8 +96,12 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
   // its K operand is fetched RS steps ahead into a small register ring.
   constexpr int NS = NKB * NKK, RS = 4;
   constexpr int NMAX = 4;                          // steps that carry the running max (8 elements each)
-  constexpr int NEXP = NS - NMAX - 1;              // steps that carry the exponentials
-  constexpr int EPS = (32 + NEXP - 1) / NEXP;      // elements per such step
+  constexpr int NEXP = NS - NMAX - 1;              // steps that carry exponentials
+  // The exponentials of the first EXP_A elements (of 32 per lane) ride along with these score
+  // MFMAs, the rest with the first half of the second product below (which only needs the first
+  // 16): one product's shadow alone is too short for all of them.
+  constexpr int EXP_A = FM_FWD_EXP_A;
+  constexpr int EPS = (EXP_A + NEXP - 1) / NEXP;   // elements per such step
   bf16x8 kring[RS];
   auto k_operand = [&](int n) __attribute__((always_inline)) {
     return *(const bf16x8*)(k_next + (n % NKB) * 32 * C::L::RS + C::L::add_col(a_b, (n / NKB) * 32));
@@ -130,7 +138,7 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
     } else {
       const int j = n - NMAX - 1;
 #pragma unroll
-      for (int e = j * EPS; e < (j + 1) * EPS && e < 32; ++e) {
+      for (int e = j * EPS; e < (j + 1) * EPS && e < EXP_A; ++e) {
         const float p = fast_exp2(__builtin_fmaf(cur[e / 16][e % 16], w.sc, neg_m));
         cur[e / 16][e % 16] = p;
         rs += p;
@@ -138,7 +146,6 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
     }
     __builtin_amdgcn_sched_barrier(0);
   }
-  l_run += rs;
 
   // ---- stream B: O^T += V^T P^T, step n = (16-key group n / NDB, d block n % NDB)
   constexpr int NP = NKB * 2 * NDB, RP = 4;
@@ -159,8 +166,18 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
     for (int e = 0; e < 8; ++e) pb[e] = (__bf16)cur[kb][8 * h + e];
     oacc[db] = mfma32(vring[n % RP], pb, oacc[db]);
     if (n + RP < NP) vring[n % RP] = v_operand(n + RP);
+    if (n < NP / 2) {   // the remaining exponentials (second 32-key block), beside the first block's MFMAs
+      constexpr int EPB = (32 - EXP_A + NP / 2 - 1) / (NP / 2);
+#pragma unroll
+      for (int e = EXP_A + n * EPB; e < EXP_A + (n + 1) * EPB && e < 32; ++e) {
+        const float p = fast_exp2(__builtin_fmaf(cur[e / 16][e % 16], w.sc, neg_m));
+        cur[e / 16][e % 16] = p;
+        rs += p;
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);
   }
+  l_run += rs;
 }
 
 // RAGGED: the sequence length is not a multiple of 128.  The loops then run at the padded length
