@@ -344,6 +344,8 @@ __device__ __forceinline__ void append_live(bool live, int entry, int* list, int
 // values already in registers, instead of re-reading the table every tile:
 //   bits 0-15  j - j_begin      bits 16-17  class of the workgroup's tile
 //   bits 18-25 class of wave w's sub-tile in bits 18+2w, 19+2w   (0 unmasked, 1 partial, 2 fully)
+//   bits 26, 27  the workgroup's tile needs the element mask of the LT / of the UT pair (Equation 4's
+//                partial test per pair; a pair whose bit is clear masks no element of the tile)
 // Returns the number of entries (uniform over the workgroup).
 __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ table, int t_c, int j_begin, int j_end,
                                                      int r0, int r1, int rows_per_wave, int* list, int* wave_cnt) {
@@ -354,7 +356,7 @@ __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ tab
     if (j < j_end) {
       const MinMax8 mm = load_minmax(table, t_c, j);
       cls = classify_tile(r0, r1, mm);
-      entry = (j - j_begin) | ((cls & 3) << 16);
+      entry = (j - j_begin) | ((cls & 3) << 16) | (((cls >> 4) & 3) << 26);
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const int w0 = min(r0 + w * rows_per_wave, r1), w1 = min(w0 + rows_per_wave, r1);
@@ -368,6 +370,8 @@ __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ tab
 __device__ __forceinline__ int entry_block(int entry, int j_begin) { return j_begin + (entry & 0xFFFF); }
 __device__ __forceinline__ int entry_tile_class(int entry) { return (entry >> 16) & 3; }
 __device__ __forceinline__ int entry_wave_class(int entry, int wave) { return (entry >> (18 + 2 * wave)) & 3; }
+// 1 = LT pair only, 2 = UT pair only, 3 = both (0 only for tiles that are not partially masked)
+__device__ __forceinline__ int entry_need_pairs(int entry) { return (entry >> 26) & 3; }
 
 // Column-parallel loop: classify row blocks [i_begin, i_end) of block_r rows
 // against one key block's min/max values; entries are i | class << 24.  The

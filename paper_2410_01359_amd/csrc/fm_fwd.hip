@@ -53,12 +53,12 @@ struct FwdWave {
 };
 
 // One pipeline step: exp / row-sum arithmetic and O^T += V^T P^T of the tile whose raw scores
-// are in `cur` (masked first if `masked`), and the raw scores of the NEXT tile (K tile at
+// are in `cur` (masked first if `masked` != 0), and the raw scores of the NEXT tile (K tile at
 // k_next) into `nxt`.
 template <int D>
 __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32x16 (&oacc)[D / 32],
                                          const bf16x8 (&qreg)[D / 16], float& m_run, float& l_run,
-                                         const char* k_next, const char* vs, const int* bnd, bool masked,
+                                         const char* k_next, const char* vs, const int* bnd, int masked,
                                          const FwdWave<D>& w) {
   using C = FwdCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
@@ -70,25 +70,45 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
 
   if (masked) {
     const int* bnd_g = (const int*)((const char*)bnd + opaque(16 * w.g));
-    // Both pairs are applied whenever the wave's sub-tile is not mask-free: a pair whose
-    // NEED bit is clear masks no element of this tile, so this is exact.  A sub-tile that
-    // Equation 4 proves fully masked takes the same path and ends with every score at -inf.
+    // A sub-tile that Equation 4 proves fully masked for this wave takes the same path and ends
+    // with every score at -inf.  `masked` says which pairs the workgroup's tile needs (1 = LT,
+    // 2 = UT, 3 = both): a pair that is not needed masks no element of the tile, so leaving it
+    // out is exact -- and most partially masked tiles (a causal diagonal, a window edge, a
+    // document boundary) need only one.
+    if (masked == 3) {
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
+      for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int kx = kb * 32 + 8 * rq;
-        const i32x4 bl = *(const i32x4*)(bnd_g + 0 * KT + kx);
-        const i32x4 be = *(const i32x4*)(bnd_g + 1 * KT + kx);
-        const i32x4 bu = *(const i32x4*)(bnd_g + 2 * KT + kx);
-        const i32x4 bv = *(const i32x4*)(bnd_g + 3 * KT + kx);
+        for (int rq = 0; rq < 4; ++rq) {
+          const int kx = kb * 32 + 8 * rq;
+          const i32x4 bl = *(const i32x4*)(bnd_g + 0 * KT + kx);
+          const i32x4 be = *(const i32x4*)(bnd_g + 1 * KT + kx);
+          const i32x4 bu = *(const i32x4*)(bnd_g + 2 * KT + kx);
+          const i32x4 bv = *(const i32x4*)(bnd_g + 3 * KT + kx);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool hit = ((w.row >= bl[e]) & (w.row < be[e])) | ((w.row >= bu[e]) & (w.row < bv[e]));
-          if (hit) cur[kb][rq * 4 + e] = -INFINITY;
+          for (int e = 0; e < 4; ++e) {
+            const bool hit = ((w.row >= bl[e]) & (w.row < be[e])) | ((w.row >= bu[e]) & (w.row < bv[e]));
+            if (hit) cur[kb][rq * 4 + e] = -INFINITY;
+          }
+          __builtin_amdgcn_sched_barrier(0);  // keep the bound reads of later steps from piling up in registers
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the bound reads of later steps from piling up in registers
-      }
+    } else {
+      const int* b_lo = bnd_g + (masked == 2 ? 2 * KT : 0);   // starts of the one pair that is needed
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int kx = kb * 32 + 8 * rq;
+          const i32x4 bs = *(const i32x4*)(b_lo + kx);
+          const i32x4 be = *(const i32x4*)(b_lo + KT + kx);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const bool hit = (w.row >= bs[e]) & (w.row < be[e]);
+            if (hit) cur[kb][rq * 4 + e] = -INFINITY;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    }
   }
 
   // ---- stream A: S^T(next) = K Q^T on the matrix unit, softmax(cur) on the vector unit.
@@ -287,7 +307,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
     FM_LOAD_V(e_1, ((T) + 1) & 1);                                                               \
     const char* vs_ = smem + C::V_OFF + ((T) & 1) * C::VSTAGE;                                   \
     fwd_step<D>(CUR, NXT, oacc, qreg, m_run, l_run, smem + C::K_OFF + (((T) + 1) & 1) * C::K_BYTES, vs_, \
-                (const int*)(vs_ + C::V_BYTES), entry_wave_class(e_t, wave) != T_UNMASKED, w);   \
+                (const int*)(vs_ + C::V_BYTES),                                                  \
+                entry_wave_class(e_t, wave) != T_UNMASKED ? entry_need_pairs(e_t) : 0, w);       \
     async_wait<0>();   /* K(T+2) and V(T+1) have landed ... */                                   \
     barrier_nofence(); /* ... for every wave, and every wave is done with K(T+1) and V(T) */     \
   }
