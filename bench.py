@@ -126,6 +126,33 @@ def run_workload(name, steps, warmup, torch, fm, orc, workloads, hip, with_event
     return res
 
 
+def forward_only_grouped(torch, fm, orc, workloads, steps):
+    """Forward pass alone at the head configuration of the paper's inference appendix (32 query
+    heads on 8 K/V heads, d = 128, batch 1) under a causal-document mask of 16 equal documents at
+    N = 32768, tensors stored [B,N,H,d]: the strided / grouped-head entry point."""
+    B, H, Hk, N, d = 1, 32, 8, 32768, 128
+    spans = workloads.spans_from_lengths([N // 16] * 16)
+    vec = workloads.causal_document_mask(N, spans)
+    vecs = tuple(torch.from_numpy(np.asarray(x, dtype=np.int32)[None]).cuda() for x in vec)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20241002)
+    q = torch.randn((B, N, H, d), device="cuda", generator=g).bfloat16().transpose(1, 2)
+    k, v = (torch.randn((B, N, Hk, d), device="cuda", generator=g).bfloat16().transpose(1, 2) for _ in range(2))
+    ws = torch.empty(fm.flashmask_workspace_bytes(fm.FM_PASS_FWD, B, H, N, d), dtype=torch.uint8, device="cuda")
+    scale = 1.0 / math.sqrt(d)
+    for _ in range(2):
+        fm.flashmask_fwd_ex(q, k, v, *vecs, scale, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fm.flashmask_fwd_ex(q, k, v, *vecs, scale, workspace=ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flop = 4.0 * d * orc.count_unmasked_elements(*vec) * H
+    return {"workload": "forward only, 32 query heads on 8 K/V heads, d=128, N=32768, causal document (16 x 2048), "
+                        "[B,N,H,d] storage", "ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1)}
+
+
 def cpu_baseline(w, orc, workloads, budget_rows):
     """The fp64 oracle, as it stands, timed on the host on a bounded sample of
     the same workload: the full forward+backward work of `budget_rows` query
@@ -253,6 +280,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
         "other_workloads": others,
+        "forward_only_grouped_heads": forward_only_grouped(torch, fm, orc, workloads, max(5, args.steps)),
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, orc, workloads, args.cpu_rows)
