@@ -280,8 +280,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
         "other_workloads": others,
-        "forward_only_grouped_heads": forward_only_grouped(torch, fm, orc, workloads, max(5, args.steps)),
     }
+    if args.others:   # the extra measurements are left out of single-workload (profiling) runs
+        line["forward_only_grouped_heads"] = forward_only_grouped(torch, fm, orc, workloads, max(5, args.steps))
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, orc, workloads, args.cpu_rows)
     print(json.dumps(line), flush=True)
