@@ -176,9 +176,24 @@ __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ wor
   __syncthreads();
   auto key_of = [&](int u) {
     const int g = by_head ? (u / units_per_bh) % kGroups : u % kGroups;
-    const int w_u = work[(u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh];
-    const int lvl = (int)(((long long)w_u * (kLevels - 1)) / (max_work > 0 ? max_work : 1));
-    return g * kLevels + (kLevels - 1 - min(max(lvl, 0), kLevels - 1));
+    const int ru = (u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh;
+    const int w_u = work[ru], mw = max_work > 0 ? max_work : 1;
+    // Heavy units (an eighth of the largest possible work or more) are ranked finely by work: their
+    // order decides how evenly the queue ends.  Lighter ones are ranked by octave of work and, within
+    // an octave, by where their live range starts: units of similar size that stream the same blocks
+    // (the rows of one document) then sit next to each other in the queue, run at the same time and
+    // share the blocks in L2.
+    constexpr int kFine = 384, kOct = 8, kPos = (kLevels - kFine) / kOct;
+    int rank;
+    if ((long long)w_u * 8 >= mw) {
+      rank = (int)(((long long)(mw - min(w_u, mw)) * 8 * (kFine - 1)) / ((long long)mw * 7));
+      rank = min(max(rank, 0), kFine - 1);
+    } else {
+      const int oct = min(max((int)__log2f((float)mw / (8.f * (float)max(w_u, 1))), 0), kOct - 1);
+      const int pos = min((int)(((long long)range[2 * ru] * kPos) / mw), kPos - 1);
+      rank = kFine + oct * kPos + pos;
+    }
+    return g * kLevels + rank;
   };
   for (int u = tid; u < total_units; u += 1024) atomicAdd(&hist[key_of(u)], 1);
   __syncthreads();
