@@ -28,6 +28,10 @@
  *     host can see are checked; bound VALUES live on the device and are not
  *     validated (the comparison above is defined for every int32).
  *   - Calls on different streams need different workspaces.
+ *   - Calls may be recorded into a HIP graph (no allocation, no host synchronisation, and the only
+ *     clears of global memory are kernels).  The first call of a kernel variant on a device raises
+ *     that kernel's dynamic-LDS limit (hipFuncSetAttribute): issue one call of the same shape class
+ *     (d, aligned or ragged N, contiguous or _ex) outside the capture first.
  */
 #ifndef FLASHMASK_H
 #define FLASHMASK_H

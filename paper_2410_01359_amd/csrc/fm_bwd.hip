@@ -788,13 +788,8 @@ hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream) {
 template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DqCfg<D>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)dq_kernel<D, RAGGED, GEN>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static bool allowed[FM_MAX_DEVICES] = {};
+  if (hipError_t e = fm_allow_lds((const void*)dq_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
   hipLaunchKernelGGL((dq_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
@@ -813,13 +808,8 @@ hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream) {
 template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DkdvCfg<D>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)dkdv_kernel<D, RAGGED, GEN>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static bool allowed[FM_MAX_DEVICES] = {};
+  if (hipError_t e = fm_allow_lds((const void*)dkdv_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
   hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dkdv)), dim3(256), C::LDS_BYTES, stream,
                      a);
   return hipGetLastError();

@@ -383,13 +383,8 @@ using namespace fm;
 template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_fwd_t(const FmFwdArgs& a, hipStream_t stream) {
   using C = FwdCfg<D>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<D, RAGGED, GEN>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static bool allowed[FM_MAX_DEVICES] = {};
+  if (hipError_t e = fm_allow_lds((const void*)fwd_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
   hipLaunchKernelGGL((fwd_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }

@@ -9,6 +9,18 @@ constexpr int FM_QUEUES = 8;
 inline int fm_order_slots(int units) { return ((units + FM_QUEUES - 1) / FM_QUEUES) * FM_QUEUES; }
 // Bytes of a pass's queue area: one 16-byte record per slot, then the FM_QUEUES queue counters.
 inline size_t fm_order_bytes(int units) { return (size_t)fm_order_slots(units) * 16 + FM_QUEUES * 4; }
+// Raise a tile-loop kernel's dynamic LDS limit once per device (the attribute belongs to the device's
+// copy of the kernel); `done` is the launcher's own flag array, one flag per device.
+constexpr int FM_MAX_DEVICES = 64;
+inline hipError_t fm_allow_lds(const void* kernel, int bytes, bool (&done)[FM_MAX_DEVICES]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < FM_MAX_DEVICES && done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev >= 0 && dev < FM_MAX_DEVICES) done[dev] = true;
+  return e;
+}
 // Workgroups of a tile-loop launch: one per slot plus a reserve of one eighth, through which the
 // XCDs that finish their own queue early take units from the others (a workgroup that finds
 // every queue empty ends at once).
