@@ -238,8 +238,11 @@ def main():
     for name in [x for x in args.others.split(",") if x and x != args.workload]:
         r = run_workload(name, max(3, args.steps // 2), 2, torch, fm, orc, workloads, hip, True)
         r.pop("workload_obj")
+        r["pct_of_bf16_mfma_peak"] = 100.0 * r["tflops"] / PEAK_BF16_TFLOPS
+        r["tile_tflops"] = r["tile_tflop"] * 1e3 / r["ms_per_step"]      # the paper's accounting: 128x128 tiles not skipped
         others.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
-                       if k in ("workload", "ms_per_step", "tflops", "block_sparsity", "fwd_ms", "bwd_ms")})
+                       if k in ("workload", "ms_per_step", "tflops", "pct_of_bf16_mfma_peak", "tile_tflops",
+                                "block_sparsity", "unmasked_tflop", "tile_tflop", "fwd_ms", "bwd_ms")})
         torch.cuda.empty_cache()
 
     if args.copy_calibration_mib > 0:
