@@ -180,6 +180,26 @@ int flashmask_preprocess(const int32_t* lts, const int32_t* lte, const int32_t* 
 int flashmask_classify(const int32_t* minmax, int B, int N, int block_r, int block_c,
                        uint8_t* cls, void* hip_stream);
 
+/*
+ * The tile scheduler's output for one pass (not in the paper; it is what balances skewed masks over
+ * the chip), exported so that it can be checked like the tables above.  Work units are row blocks
+ * (FM_PASS_FWD, FM_PASS_BWD_DQ) or key blocks (FM_PASS_BWD_DKDV) of the pass's tile shape, numbered
+ * (b * H + h) * T + block.  They are dealt to 8 queues; slot s belongs to queue s % 8 and holds the
+ * (s / 8)-th unit that queue hands out:
+ *   records  out  int32 [slots, 4] = {unit or -1 (no unit), first block of the unit's live range,
+ *                 one past its last (0, 0 if every tile of the unit is fully masked), 0}
+ *   slots    out  HOST int: number of slots (a multiple of 8, >= B * H * T); with records == NULL
+ *                 the call only reports it.
+ * Every unit appears exactly once; tiles outside a unit's live range are fully masked (Equation 4);
+ * within a queue the units holding at least an eighth of the largest possible work come first, by
+ * falling work, then the lighter ones by falling octave of work.  workspace as for the pass
+ * (FM_PASS_FWD for the forward, FM_PASS_BWD otherwise); the records are copied out of it on the
+ * stream.  N here is rounded up to a multiple of 128 (T counts blocks of the padded length).
+ */
+int flashmask_unit_queues(int pass, const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                          int B, int H, int N, int d, int32_t* records, int* slots,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Tile shape (rows x key columns) at which the given pass classifies and skips
  * tiles.  Host-only. */
 int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c);

@@ -50,6 +50,8 @@ def load_library() -> ctypes.CDLL:
     lib.flashmask_fwd_ex.argtypes = [vp, vp, vp, ip, ip, ip, ip, f, vp, fp, i, i, i, i, i, sp, sp, sp, sp, vp, sz, vp]
     lib.flashmask_bwd_ex.restype = i
     lib.flashmask_bwd_ex.argtypes = [vp, vp, vp, vp, fp, vp, ip, ip, ip, ip, f, vp, vp, vp, i, i, i, i, i, sp, vp, sz, vp]
+    lib.flashmask_unit_queues.restype = i
+    lib.flashmask_unit_queues.argtypes = [i, ip, ip, ip, ip, i, i, i, i, ip, ctypes.POINTER(i), vp, sz, vp]
     lib.flashmask_workspace_bytes.restype = sz
     lib.flashmask_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.flashmask_preprocess.restype = i
@@ -229,3 +231,20 @@ def flashmask_bwd_ex(q, k, v, out, lse, dout, lts, lte, uts, ute, scale: float,
                                            B, H, Hk, N, d, arr, ws.data_ptr(), ws.numel(), _stream()),
            "flashmask_bwd_ex")
     return dq, dk, dv
+
+
+def flashmask_unit_queues(pass_id: int, lts, lte, uts, ute, H: int, d: int) -> torch.Tensor:
+    """int32 [slots, 4] slot records of the pass's unit queues (see flashmask.h)."""
+    vecs = [_dev(x, torch.int32, n) for x, n in zip((lts, lte, uts, ute), ("lts", "lte", "uts", "ute"))]
+    B, N = vecs[0].shape
+    lib = load_library()
+    slots = ctypes.c_int(0)
+    ptrs = [v.data_ptr() for v in vecs]
+    _check(lib.flashmask_unit_queues(pass_id, *ptrs, B, H, N, d, None, ctypes.byref(slots), None, 0, None),
+           "flashmask_unit_queues")
+    rec = torch.empty((slots.value, 4), dtype=torch.int32, device=vecs[0].device)
+    ws = _workspace(flashmask_workspace_bytes(FM_PASS_FWD if pass_id == FM_PASS_FWD else FM_PASS_BWD, B, H, N, d),
+                    vecs[0].device)
+    _check(lib.flashmask_unit_queues(pass_id, *ptrs, B, H, N, d, rec.data_ptr(), ctypes.byref(slots), ws.data_ptr(),
+                                     ws.numel(), _stream()), "flashmask_unit_queues")
+    return rec

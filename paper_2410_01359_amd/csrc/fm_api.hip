@@ -191,6 +191,45 @@ static int fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
   return FM_OK;
 }
 
+int flashmask_unit_queues(int pass, const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                          int B, int H, int N, int d, int32_t* records, int* slots, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  if (!lts || !lte || !uts || !ute || !slots) return FM_ERR_NULL;
+  if (int rc = check_shape(B, H, N, d)) return rc;
+  if (pass != FM_PASS_FWD && pass != FM_PASS_BWD_DQ && pass != FM_PASS_BWD_DKDV) return FM_ERR_ARG;
+  const bool rows = pass != FM_PASS_BWD_DKDV;
+  const int br = pass == FM_PASS_FWD ? FM_FWD_BR : rows ? FM_DQ_BR : FM_DKDV_BR;
+  const int bc = pass == FM_PASS_FWD ? FM_FWD_BC : rows ? FM_DQ_BC : FM_DKDV_BC;
+  const int Np = padded_len(N);
+  *slots = fm_order_slots(B * H * (Np / (rows ? br : bc)));
+  if (!records) return FM_OK;   // size query
+  if (misaligned(lts) || misaligned(lte) || misaligned(uts) || misaligned(ute) || misaligned(records)) return FM_ERR_ALIGN;
+  const size_t need = flashmask_workspace_bytes(rows && pass == FM_PASS_FWD ? FM_PASS_FWD : FM_PASS_BWD, B, H, N, d);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FM_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  hipError_t e;
+  if (Np != N) {
+    int* padded = (int*)ws;
+    e = fm_launch_pad_bounds(lts, lte, uts, ute, B, N, Np, padded, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    const size_t plane = (size_t)B * Np;
+    lts = padded; lte = padded + plane; uts = padded + 2 * plane; ute = padded + 3 * plane;
+    ws += padded_bounds_bytes(B, N);
+  }
+  const PassSpace sp = pass_space(B, H, Np, br, bc, rows, 0);
+  int* minmax = (int*)(ws + sp.minmax);
+  e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, bc, minmax, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = rows ? fm_launch_row_order(minmax, B, H, Np, br, bc, (int*)(ws + sp.work), (int*)(ws + sp.range),
+                                 (int*)(ws + sp.order), stream)
+           : fm_launch_col_order(minmax, B, H, Np, br, bc, (int*)(ws + sp.work), (int*)(ws + sp.range),
+                                 (int*)(ws + sp.order), stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipMemcpyAsync(records, ws + sp.order, (size_t)*slots * 16, hipMemcpyDeviceToDevice, stream);
+  return e == hipSuccess ? FM_OK : hip_fail(e);
+}
+
 int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
                   const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H, int N,
                   int d, void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -40,3 +40,68 @@ def test_tables_at_config_sizes_and_kernel_tile_shapes(name):
         br, bc = fm.flashmask_tile_shape(p, w.d)
         _tables_equal(w.vectors, w.N, br, bc)
     _tables_equal(w.vectors, w.N, 128, 128)
+
+
+def _check_unit_queues(w, pass_id):
+    """Invariants of the tile scheduler's output (the library's own addition to the method):
+    every unit exactly once, live ranges as Equation 4 gives them, queue membership by head,
+    heavy units first and by falling work."""
+    import paper_2410_01359_amd as fm
+    vecs = tuple(torch.from_numpy(x).cuda() for x in w.stacked_vectors())
+    rec = fm.flashmask_unit_queues(pass_id, *vecs, w.H, w.d)
+    torch.cuda.synchronize()
+    rec = rec.cpu().numpy()
+    br, bc = fm.flashmask_tile_shape(pass_id, w.d)
+    rows = pass_id != fm.FM_PASS_BWD_DKDV
+    T = w.N // (br if rows else bc)
+    units = w.B * w.H * T
+    assert rec.shape[0] % 8 == 0 and rec.shape[0] >= units
+    ids = rec[:, 0]
+    assert np.array_equal(np.sort(ids[ids >= 0]), np.arange(units)), "every unit exactly once"
+    assert np.all(rec[ids < 0, 1:] == 0) and np.all(rec[:, 3] == 0)
+    # live range and work of every unit from the oracle's tile classes
+    lo_ref, hi_ref, work_ref = (np.zeros((w.B, T), dtype=np.int64) for _ in range(3))
+    for b, v in enumerate(w.vectors):
+        live = orc.tile_kind(orc.classify_tiles_fast(orc.minmax_tables(*v, bc), w.N, br, bc)) != orc.FULLY
+        live = live if rows else live.T                     # [unit block, scanned block]
+        work_ref[b] = live.sum(axis=1)
+        any_live = work_ref[b] > 0
+        lo_ref[b] = np.where(any_live, live.argmax(axis=1), 0)
+        hi_ref[b] = np.where(any_live, live.shape[1] - live[:, ::-1].argmax(axis=1), 0)
+    slot = np.nonzero(ids >= 0)[0]
+    u = ids[slot].astype(np.int64)
+    bh, blk = u // T, u % T
+    b = bh // w.H
+    assert np.array_equal(rec[slot, 1], lo_ref[b, blk]) and np.array_equal(rec[slot, 2], hi_ref[b, blk])
+    if (w.B * w.H) % 8 == 0:
+        assert np.array_equal(slot % 8, bh % 8), "a head's units share one queue"
+    max_work = w.N // (bc if rows else br)
+    for q in range(8):
+        s_q = slot[slot % 8 == q]
+        work = work_ref[b[slot % 8 == q], blk[slot % 8 == q]][np.argsort(s_q)]
+        heavy = work * 8 >= max_work
+        if heavy.any():
+            assert not heavy[np.argmin(heavy):].any() or heavy.all(), "heavy units come first"
+            hw = work[heavy]
+            level = max(1, -(-7 * max_work // (8 * 383)))   # work span of one of the 384 fine ranks
+            assert np.all(hw[:-1] + level >= hw[1:]), "heavy units by falling work (to the rank's resolution)"
+        light = work[~heavy]
+        if light.size:
+            octave = np.floor(np.log2(max_work / (8.0 * np.maximum(light, 1)))).clip(0, 7)
+            assert np.all(np.diff(octave) >= 0), "lighter units by falling octave of work"
+
+
+@pytest.mark.parametrize("name", ["1", "2", "3", "4a", "4b", "5"])
+def test_unit_queues_at_config_sizes(name):
+    import paper_2410_01359_amd as fm
+    w = workloads.config(name)
+    for p in (fm.FM_PASS_FWD, fm.FM_PASS_BWD_DQ, fm.FM_PASS_BWD_DKDV):
+        _check_unit_queues(w, p)
+
+
+@pytest.mark.parametrize("kind", ["full", "document", "random_intervals", "global_sliding_window"])
+def test_unit_queues_small_families(kind):
+    import paper_2410_01359_amd as fm
+    w = workloads.small_workload(kind, 1536, seed=11, B=3, H=5, d=64)    # B * H not a multiple of 8
+    for p in (fm.FM_PASS_FWD, fm.FM_PASS_BWD_DQ, fm.FM_PASS_BWD_DKDV):
+        _check_unit_queues(w, p)
