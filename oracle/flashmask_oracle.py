@@ -41,7 +41,8 @@ defining predicate by brute force; the interval example printed in Section 4.1;
 textbook softmax attention for the empty mask; closed forms for Q = 0; rows of
 P sum to one; gradients vs central finite differences; tables vs brute force;
 tile counts and TFLOP figures printed in the paper's kernel tables for the
-deterministic masks.  The random document / shared-question workloads of the
+deterministic masks; the grouped-head gradients vs finite differences of the
+summed loss.  The random document / shared-question workloads of the
 paper are unpublished: for those inputs parity is pinned only by predicates,
 closed forms and invariants ("parity unpinned" by printed values).
 """
@@ -171,6 +172,30 @@ def backward(q, k, v, dout, lts, lte, uts, ute, scale):
         dq[r], dk_part, dv_part, out[r], lse[r] = backward_row_block(q, k, v, dout, lts, lte, uts, ute, scale, r)
         dk += dk_part
         dv += dv_part
+    return dq, dk, dv, out, lse
+
+
+def backward_grouped(q, k, v, dout, lts, lte, uts, ute, scale):
+    """Grouped K/V heads (the head layout of the paper's inference appendix: H query heads on
+    H_kv < H key/value heads; query head h attends to K/V head h // (H // H_kv)).
+
+    q, dout: [H, N, d]; k, v: [H_kv, N, d].  Each query head is plain attention on its K/V head;
+    a K/V head's gradient is the sum of what its query heads send back (chain rule through the
+    shared tensor).  Returns dq [H,N,d], dk, dv [H_kv,N,d], out [H,N,d], lse [H,N].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    heads, kv_heads = q.shape[0], k.shape[0]
+    assert heads % kv_heads == 0
+    group = heads // kv_heads
+    dq = np.zeros_like(q); dk = np.zeros_like(k); dv = np.zeros_like(v)
+    out = np.zeros_like(dout); lse = np.zeros(q.shape[:2])
+    for h in range(heads):
+        dq[h], dk_h, dv_h, out[h], lse[h] = backward(q[h], k[h // group], v[h // group], dout[h], lts, lte, uts, ute, scale)
+        dk[h // group] += dk_h
+        dv[h // group] += dv_h
     return dq, dk, dv, out, lse
 
 

@@ -97,3 +97,33 @@ def test_partial_backward_helpers_equal_full():
     assert np.allclose(orc.backward_rows(q, k, v, do, *vec, 0.25, rows), dq[rows], atol=1e-13)
     dk2, dv2 = orc.backward_cols(q, k, v, do, *vec, 0.25, cols)
     assert np.allclose(dk2, dk[cols], atol=1e-13) and np.allclose(dv2, dv[cols], atol=1e-13)
+
+
+@pytest.mark.parametrize("heads,kv_heads", [(4, 2), (3, 1), (6, 3)])
+def test_grouped_head_gradients_match_central_finite_differences(heads, kv_heads):
+    """K/V heads shared by several query heads: dk, dv of a K/V head are the derivatives of the
+    loss summed over ALL heads, which is what finite differences of that loss see."""
+    n, d, scale = 12, 4, 0.7
+    w = workloads.small_workload("causal_document", n, seed=41)
+    vec = w.vectors[0]
+    rng = np.random.default_rng(17)
+    q, do = rng.standard_normal((heads, n, d)), rng.standard_normal((heads, n, d))
+    k, v = rng.standard_normal((kv_heads, n, d)), rng.standard_normal((kv_heads, n, d))
+    dq, dk, dv, out, lse = orc.backward_grouped(q, k, v, do, *vec, scale)
+    group = heads // kv_heads
+
+    def loss(q_, k_, v_):
+        return sum(float((orc.forward(q_[h], k_[h // group], v_[h // group], *vec, scale)[0] * do[h]).sum())
+                   for h in range(heads))
+
+    eps = 1e-6
+    for arr, grad, which in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        for _ in range(10):
+            idx = tuple(int(rng.integers(sz)) for sz in arr.shape)
+            args = [q.copy(), k.copy(), v.copy()]
+            args[which][idx] += eps
+            up = loss(*args)
+            args[which][idx] -= 2 * eps
+            dn = loss(*args)
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - grad[idx]) < 1e-7 * max(1.0, abs(fd)), (which, idx, fd, grad[idx])
