@@ -215,8 +215,8 @@ const char* flashmask_last_hip_error(void);
  * handles of already-created hipEvent_t objects.  While registered, every
  * flashmask_fwd / flashmask_bwd call records them on its stream between its
  * internal launches, so a benchmark can time one kernel inside the call:
- *   forward : [0] entry, [1] after preprocessing + launch order, [2] after the tile loop
- *   backward: [0] entry, [1] after preprocessing + launch orders, [2] after the
+ *   forward : [0] entry, [1] after preprocessing + unit queues, [2] after the tile loop
+ *   backward: [0] entry, [1] after preprocessing + unit queues, [2] after the
  *             D pre-pass, [3] after the dK/dV loop, [4] after the dQ loop
  * The array must stay valid until cleared with (NULL, 0).  Process-global and
  * not thread-safe; entries that are NULL or beyond `count` are skipped.

@@ -56,7 +56,7 @@ inline size_t padded_bounds_bytes(int B, int N) {
   return padded_len(N) == N ? 0 : align_up((size_t)4 * B * padded_len(N) * 4, 256);
 }
 
-// Workspace layout of a pass: tables, work counts and launch order.
+// Workspace layout of a pass: tables, work counts and unit queues.
 struct PassSpace {
   size_t minmax, work, range, order, total;
 };

@@ -157,14 +157,6 @@ __device__ __forceinline__ void async_copy16(const void* gsrc, unsigned lds_addr
                : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gsrc)
                : "memory", "m0");
 }
-// Same copy with the global address given as a wave-uniform base (scalar registers) plus a
-// 32-bit per-lane byte offset: no per-copy vector address arithmetic.
-__device__ __forceinline__ void async_copy16_sbase(const void* uniform_base, unsigned lane_byte_off, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_byte_off), "s"(uniform_base)
-               : "memory", "m0");
-}
 // Copy by lanes 0..7 only (128 bytes to lds_addr), whatever the wave's execution mask is;
 // the mask is narrowed and restored inside the statement, so no branch is needed around it.
 __device__ __forceinline__ void async_copy16_lanes8(const void* gsrc, unsigned lds_addr) {
@@ -277,10 +269,10 @@ __device__ __forceinline__ int opaque(int x) {
 }
 
 // Unit queues.  Workgroup x draws a ticket from queue x % FM_QUEUES (ticket t of queue g is slot
-// t * FM_QUEUES + g of the launch order); when that queue is used up it draws from the queue that
+// t * FM_QUEUES + g of the slot records); when that queue is used up it draws from the queue that
 // has most left, and when all are used up it gets nothing.  Returns the slot record, wave-uniform,
 // with unit = -1 for "nothing".  One barrier; lds_word is a scratch word in LDS.  The counters sit
-// behind the slot records and are zeroed by the launch-order kernel of every call.
+// behind the slot records and are zeroed by the queue-building kernel of every call.
 __device__ __forceinline__ i32x4 queue_take(int* order, int slots, int* lds_word) {
   if (threadIdx.x == 0) {
     int* counters = order + 4 * (size_t)slots;

@@ -208,7 +208,7 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
 template <int D, bool RAGGED, bool GEN>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   using C = FwdCfg<D>;
-  constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16, QB = 1;
+  constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const i32x4 rec = queue_take(a.order, a.slots, (int*)(smem + C::CNT_OFF) + 8);
@@ -356,11 +356,10 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
   __bf16* op = (__bf16*)slice_ptr<D, GEN>(a.out, a.so, b, h, H, Nr);
   const int o_rs = row_stride<D, GEN>(a.so);
   float* lp = a.lse + (size_t)bh * Nr;
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
+  {
     const float lt = l_run + partner32(l_run);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
-    const int row = qw0 + qb * 32 + c;
+    const int row = qw0 + c;
     if (!RAGGED || row < Nr) {
 #pragma unroll
       for (int db = 0; db < NDB; ++db)

@@ -26,10 +26,6 @@ inline hipError_t fm_allow_lds(const void* kernel, int bytes, bool (&done)[FM_MA
 // every queue empty ends at once).
 inline int fm_launch_grid(int slots) { return slots + fm_order_slots(slots / 8); }
 
-struct FmShape {
-  int B, H, N, d;
-};
-
 // Tile shapes (rows x key columns) each pass classifies at.
 constexpr int FM_FWD_BR = 128, FM_FWD_BC = 64;
 constexpr int FM_DQ_BR = 128, FM_DQ_BC = 64;

@@ -1,6 +1,6 @@
 // Preprocessing (Section 4.2): per key-block min/max of the four bound vectors,
-// the exported tile-class dump (Equation 4), and the per-unit work counts the
-// launch order is built from.
+// the exported tile-class dump (Equation 4), the per-unit work counts, and
+// the unit queues built from them.
 #include <climits>
 
 #include "fm_common.h"
