@@ -205,7 +205,7 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, help="1, 2, 3, 4a, 4b or 5")
     ap.add_argument("--others", default="2,3,4a,4b", help="extra workloads reported in `other_workloads` ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--cpu-rows", type=int, default=12288)
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, print the block-sparsity sweep (time vs 1 - sparsity)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
