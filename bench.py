@@ -197,6 +197,29 @@ def sparsity_sweep(torch, fm, orc, workloads, hip, steps, warmup):
             "points": pts}
 
 
+def paper_table(torch, fm, orc, workloads, hip, steps, warmup):
+    """Forward and backward time at the shapes of the paper's kernel-speed tables (d = 128, 128K tokens,
+    32 heads, N = 8K / 32K / 128K; the rows whose masks have no random structure), with the paper's own
+    FLOP accounting (128 x 128 tiles not skipped) next to the strict one (unmasked elements)."""
+    rows = []
+    for w in workloads.paper_table_workloads():
+        r = run_workload(w, steps, warmup, torch, fm, orc, workloads, hip, True)
+        fw_tile = r["tile_tflop"] / 3.5
+        rows.append({"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "block_sparsity": round(r["block_sparsity"], 4),
+                     "fwd_ms": round(r["fwd_ms"], 3), "bwd_ms": round(r["bwd_ms"], 3), "total_ms": round(r["ms_per_step"], 3),
+                     "tile_tflop_fwd": round(fw_tile, 2), "tile_tflop_bwd": round(2.5 * fw_tile, 2),
+                     "fwd_tile_tflops": round(fw_tile * 1e3 / r["fwd_ms"], 1),
+                     "bwd_tile_tflops": round(2.5 * fw_tile * 1e3 / r["bwd_ms"], 1),
+                     "total_tile_tflops": round(r["tile_tflop"] * 1e3 / r["ms_per_step"], 1),
+                     "total_unmasked_tflops": round(r["tflops"], 1),
+                     "pct_of_bf16_mfma_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2)})
+        print(f"# {rows[-1]}", file=sys.stderr, flush=True)
+        del r
+        torch.cuda.empty_cache()
+    return {"metric": "fwd / bwd / total TFLOP/s at the shapes of the paper's d=128 kernel-speed tables, 1 MI355X",
+            "steps": steps, "warmup": warmup, "dtype": "bf16", "data": "synthetic", "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +231,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=12288)
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, print the block-sparsity sweep (time vs 1 - sparsity)")
+    ap.add_argument("--paper-table", action="store_true",
+                    help="instead of the benchmark line, time the deterministic rows of the paper's d=128 "
+                         "kernel-speed tables (128K tokens, 32 heads, N = 8K / 32K / 128K)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (read once, written once): a kernel of known "
                          "HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -230,6 +256,10 @@ def main():
 
     if args.sweep:
         print(json.dumps(sparsity_sweep(torch, fm, orc, workloads, hip, max(3, args.steps // 4), 2)), flush=True)
+        return
+
+    if args.paper_table:
+        print(json.dumps(paper_table(torch, fm, orc, workloads, hip, max(2, args.steps // 5), 1)), flush=True)
         return
 
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, fm, orc, workloads, hip, True)

@@ -6,6 +6,9 @@
 // The tile loops draw their work units from FM_QUEUES interleaved queues (one per XCD).
 constexpr int FM_QUEUES = 8;
 // Number of queue slots for `units` work units.
+// Slices (batch row, head) of a queue that are ranked together, longest first; a queue works its
+// groups off one after the other.
+constexpr int FM_QUEUE_CHUNK = 2;
 inline int fm_order_slots(int units) { return ((units + FM_QUEUES - 1) / FM_QUEUES) * FM_QUEUES; }
 // Bytes of a pass's queue area: one 16-byte record per slot, then the FM_QUEUES queue counters.
 inline size_t fm_order_bytes(int units) { return (size_t)fm_order_slots(units) * 16 + FM_QUEUES * 4; }

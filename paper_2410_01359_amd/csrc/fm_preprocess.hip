@@ -144,24 +144,38 @@ __global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ m
   }
 }
 
-// Launch order (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8.
-// Units are dealt into 8 queues (one per XCD: by head when the head count is a
-// multiple of 8, so that the units sharing one head's K/V also share one L2),
-// each queue is sorted heaviest first (work quantised to 512 levels), and the
-// queues are interleaved: slot 8*s + g = s-th heaviest unit of queue g.  A
-// workgroup draws the next ticket of its XCD's queue when it starts, so every
-// queue is worked off longest-job-first; the launch holds more workgroups than
-// there are slots, and a workgroup that finds its own queue empty draws from the
-// queue that has most left.  (The XCDs do not run at the same speed: with equal
-// shares the slowest one finishes about a tenth later than the fastest.)
+// Unit queues (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8.
+// Units are dealt into 8 queues (one per XCD: by slice (batch row, head) when the
+// slice count is a multiple of 8, so that the units sharing one head's K/V also
+// share one L2), each queue is sorted heaviest first within groups of slices (see
+// order_kernel; work quantised to 512 levels), and the queues are interleaved:
+// slot 8*s + g = position s of queue g.  A workgroup draws the next ticket of its
+// XCD's queue when it starts, so every queue is worked off longest-job-first; the
+// launch holds more workgroups than there are slots, and a workgroup that finds its
+// own queue empty draws from the queue that has most left.  (The XCDs do not run
+// at the same speed: with equal shares the slowest one finishes about a tenth
+// later than the fastest.)
 // A slot is the record {unit, first live block, one past the last live block, 0},
 // so a workgroup learns all it needs to start from one 16-byte load; slots with
 // no unit hold unit = -1.  The kernel also zeroes the 8 queue counters behind
-// the slots.  Single workgroup of 1024 threads.
+// the slots.  Workgroups of 1024 threads.
 constexpr int kLevels = 512;
 constexpr int kGroups = FM_QUEUES;
+// workgroups of the queue-building launch: one per FM_QUEUE_CHUNK slices of every queue when slices go to
+// queues whole, else one
+static inline int fm_order_grid(int B, int H) {
+  return (B * H) % FM_QUEUES == 0 ? ((B * H) / FM_QUEUES + FM_QUEUE_CHUNK - 1) / FM_QUEUE_CHUNK : 1;
+}
 
 // work and range are indexed [batch row][block]; a unit is (batch row, head, block).
+// When batch * heads is a multiple of the queue count, slice (batch row, head) number s goes to queue
+// s % 8 whole, and a queue holds its slices in groups of FM_QUEUE_CHUNK, one group after the other:
+// the units that run at the same time then belong to few slices and share their K/V (or Q/dO) in the
+// XCD's L2 and in the memory-side cache.  (Ranking a queue's units of ALL slices by work alone spreads
+// the resident workgroups over as many slices as the queue has; with 64 slices per queue the loops
+// then stream from HBM and lose a quarter of their rate.)  Workgroup x of this launch sorts group x of
+// every queue.  Otherwise one workgroup deals all units round-robin.  Within a group (or the whole
+// set) units are ranked as key_of() describes.
 __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ work, const int* __restrict__ range,
                                                      int batch, int heads, int units_per_bh, int max_work, int slots,
                                                      i32x4* __restrict__ order, int* __restrict__ counters) {
@@ -170,9 +184,16 @@ __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ wor
   const int tid = threadIdx.x;
   const int total_units = batch * heads * units_per_bh;
   const bool by_head = ((batch * heads) % kGroups) == 0;
+  constexpr int chunk = FM_QUEUE_CHUNK;
+  const int u_begin = by_head ? blockIdx.x * chunk * kGroups * units_per_bh : 0;
+  const int u_end = by_head ? min(u_begin + chunk * kGroups * units_per_bh, total_units) : total_units;
+  const int pos_base = by_head ? blockIdx.x * chunk * units_per_bh : 0;   // first queue position of this workgroup's units
   for (int w = tid; w < kGroups * kLevels; w += 1024) hist[w] = 0;
-  for (int s = tid; s < slots; s += 1024) order[s] = i32x4{-1, 0, 0, 0};
-  if (tid < kGroups) counters[tid] = 0;
+  if (blockIdx.x == 0) {
+    // by head every queue is filled exactly to total_units / 8; dealt round-robin the last row may have holes
+    for (int s = (by_head ? total_units : 0) + tid; s < slots; s += 1024) order[s] = i32x4{-1, 0, 0, 0};
+    if (tid < kGroups) counters[tid] = 0;
+  }
   __syncthreads();
   auto key_of = [&](int u) {
     const int g = by_head ? (u / units_per_bh) % kGroups : u % kGroups;
@@ -195,7 +216,7 @@ __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ wor
     }
     return g * kLevels + rank;
   };
-  for (int u = tid; u < total_units; u += 1024) atomicAdd(&hist[key_of(u)], 1);
+  for (int u = u_begin + tid; u < u_end; u += 1024) atomicAdd(&hist[key_of(u)], 1);
   __syncthreads();
   // exclusive scan of hist (4096 entries, 4 per thread)
   int v[4], sum = 0;
@@ -225,10 +246,10 @@ __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ wor
   __shared__ int group_start[kGroups];
   if (tid < kGroups) group_start[tid] = hist[tid * kLevels];
   __syncthreads();
-  for (int u = tid; u < total_units; u += 1024) {
+  for (int u = u_begin + tid; u < u_end; u += 1024) {
     const int key = key_of(u);
     const int g = key / kLevels;
-    const int pos = atomicAdd(&hist[key], 1) - group_start[g];
+    const int pos = pos_base + atomicAdd(&hist[key], 1) - group_start[g];
     const int slot = pos * kGroups + g;
     const int ru = (u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh;
     if (slot < slots) order[slot] = i32x4{u, range[2 * ru], range[2 * ru + 1], 0};
@@ -273,7 +294,7 @@ hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block
   hipLaunchKernelGGL(row_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
   const int slots = fm_order_slots(B * H * t_r);
-  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, range, B, H, t_r, t_c, slots, (i32x4*)order,
+  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream, work, range, B, H, t_r, t_c, slots, (i32x4*)order,
                      order + 4 * (size_t)slots);
   return hipGetLastError();
 }
@@ -286,7 +307,7 @@ hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block
   hipLaunchKernelGGL(col_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
   const int slots = fm_order_slots(B * H * t_c);
-  hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, stream, work, range, B, H, t_c, t_r, slots, (i32x4*)order,
+  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream, work, range, B, H, t_c, t_r, slots, (i32x4*)order,
                      order + 4 * (size_t)slots);
   return hipGetLastError();
 }

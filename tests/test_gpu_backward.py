@@ -54,6 +54,14 @@ def test_backward_ragged_lengths(kind, N, d):
     compare_all(w, *run_fwd_bwd(w), f"{kind} N={N} d={d}")
 
 
+@pytest.mark.parametrize("kind", ["causal_document", "random_intervals"])
+def test_backward_many_slices(kind):
+    """40 (batch row, head) slices: five per unit queue, i.e. three groups of slices per queue, the
+    last one partial, each batch row with its own mask."""
+    w = workloads.small_workload(kind, 384, seed=83, B=5, H=8, d=64)
+    compare_all(w, *run_fwd_bwd(w), f"{kind} B=5 H=8")
+
+
 def test_backward_config1_all_heads():
     w = workloads.config("1")
     compare_all(w, *run_fwd_bwd(w), "config 1")

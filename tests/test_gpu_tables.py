@@ -45,7 +45,7 @@ def test_tables_at_config_sizes_and_kernel_tile_shapes(name):
 def _check_unit_queues(w, pass_id):
     """Invariants of the tile scheduler's output (the library's own addition to the method):
     every unit exactly once, live ranges as Equation 4 gives them, queue membership by head,
-    heavy units first and by falling work."""
+    a queue's slices in groups, and within a group heavy units first and by falling work."""
     import paper_2410_01359_amd as fm
     vecs = tuple(torch.from_numpy(x).cuda() for x in w.stacked_vectors())
     rec = fm.flashmask_unit_queues(pass_id, *vecs, w.H, w.d)
@@ -76,19 +76,29 @@ def _check_unit_queues(w, pass_id):
     if (w.B * w.H) % 8 == 0:
         assert np.array_equal(slot % 8, bh % 8), "a head's units share one queue"
     max_work = w.N // (bc if rows else br)
+    by_slice = (w.B * w.H) % 8 == 0
+    chunk = 2                      # slices of a queue that are ranked together (FM_QUEUE_CHUNK)
     for q in range(8):
-        s_q = slot[slot % 8 == q]
-        work = work_ref[b[slot % 8 == q], blk[slot % 8 == q]][np.argsort(s_q)]
-        heavy = work * 8 >= max_work
-        if heavy.any():
-            assert not heavy[np.argmin(heavy):].any() or heavy.all(), "heavy units come first"
-            hw = work[heavy]
-            level = max(1, -(-7 * max_work // (8 * 383)))   # work span of one of the 384 fine ranks
-            assert np.all(hw[:-1] + level >= hw[1:]), "heavy units by falling work (to the rank's resolution)"
-        light = work[~heavy]
-        if light.size:
-            octave = np.floor(np.log2(max_work / (8.0 * np.maximum(light, 1)))).clip(0, 7)
-            assert np.all(np.diff(octave) >= 0), "lighter units by falling octave of work"
+        in_q = slot % 8 == q
+        pos = slot[in_q] // 8
+        order_q = np.argsort(pos)
+        pos, work_q, bh_q = pos[order_q], work_ref[b[in_q], blk[in_q]][order_q], bh[in_q][order_q]
+        # a queue holds its slices in groups of `chunk`, one group after the other; ranking is per group
+        seg = pos // (chunk * T) if by_slice else np.zeros_like(pos)
+        if by_slice:
+            assert np.array_equal(seg, (bh_q // 8) // chunk), "a queue's slices in groups, one group after the other"
+        for sg in np.unique(seg):
+            work = work_q[seg == sg]
+            heavy = work * 8 >= max_work
+            if heavy.any():
+                assert not heavy[np.argmin(heavy):].any() or heavy.all(), "heavy units come first"
+                hw = work[heavy]
+                level = max(1, -(-7 * max_work // (8 * 383)))   # work span of one of the 384 fine ranks
+                assert np.all(hw[:-1] + level >= hw[1:]), "heavy units by falling work (to the rank's resolution)"
+            light = work[~heavy]
+            if light.size:
+                octave = np.floor(np.log2(max_work / (8.0 * np.maximum(light, 1)))).clip(0, 7)
+                assert np.all(np.diff(octave) >= 0), "lighter units by falling octave of work"
 
 
 @pytest.mark.parametrize("name", ["1", "2", "3", "4a", "4b", "5"])
@@ -103,5 +113,14 @@ def test_unit_queues_at_config_sizes(name):
 def test_unit_queues_small_families(kind):
     import paper_2410_01359_amd as fm
     w = workloads.small_workload(kind, 1536, seed=11, B=3, H=5, d=64)    # B * H not a multiple of 8
+    for p in (fm.FM_PASS_FWD, fm.FM_PASS_BWD_DQ, fm.FM_PASS_BWD_DKDV):
+        _check_unit_queues(w, p)
+
+
+@pytest.mark.parametrize("B,H", [(5, 8), (3, 16), (1, 8)])
+def test_unit_queues_many_slices(B, H):
+    """Slice counts that give a queue several groups of slices, the last one partial."""
+    import paper_2410_01359_amd as fm
+    w = workloads.small_workload("causal_document", 2048, seed=13, B=B, H=H, d=128)
     for p in (fm.FM_PASS_FWD, fm.FM_PASS_BWD_DQ, fm.FM_PASS_BWD_DKDV):
         _check_unit_queues(w, p)

@@ -315,6 +315,30 @@ def sweep_workloads(n_random: int = 20):
     return out
 
 
+def paper_table_workloads():
+    """The deterministic rows of the paper's kernel-speed tables for head dim 128 (appendix on kernel
+    performance): 128K tokens in total, 32 heads, sequence length 8K / 32K / 128K (batch 16 / 4 / 1),
+    masks Full, Causal, Sliding window and Prefix-LM.  The paper states neither the window width nor the
+    prefix length; its printed FLOPs fit window = N/16 and prefix = N/2 on 128 x 128 accounting tiles."""
+    out = []
+    for k, N in enumerate((8192, 32768, 131072)):
+        B = 131072 // N
+        for m, kind in enumerate(("full", "causal", "sliding_window", "prefix_lm")):
+            w = Workload(f"table-{kind}-{N // 1024}K", B, 32, N, 128, BASE_SEED + 700 + 10 * k + m, kind)
+            if kind == "full":
+                st, vec = {}, full_mask(N)
+            elif kind == "causal":
+                st, vec = {}, causal_mask(N)
+            elif kind == "sliding_window":
+                st, vec = {"window": N // 16}, sliding_window_mask(N, N // 16)
+            else:
+                st, vec = {"prefix": N // 2}, prefix_lm_mask(N, N // 2)
+            w.structure = [st] * B
+            w.vectors = [vec] * B
+            out.append(w)
+    return out
+
+
 def small_workload(mask_kind: str, N: int, seed: int, B: int = 1, H: int = 1, d: int = 64) -> Workload:
     """Small seeded case of any mask family, for parity tests."""
     w = Workload(f"small-{mask_kind}-{N}", B, H, N, d, seed, mask_kind)
