@@ -190,8 +190,11 @@ int flashmask_classify(const int32_t* minmax, int B, int N, int block_r, int blo
  *                 one past its last (0, 0 if every tile of the unit is fully masked), 0}
  *   slots    out  HOST int: number of slots (a multiple of 8, >= B * H * T); with records == NULL
  *                 the call only reports it.
- * Every unit appears exactly once; tiles outside a unit's live range are fully masked (Equation 4);
- * within a queue the units holding at least an eighth of the largest possible work come first, by
+ * Every unit appears exactly once; tiles outside a unit's live range are fully masked (Equation 4).
+ * Slices (b, h) go to queues whole, slice b * H + h to queue (b * H + h) % 8, while they fill rounds
+ * of 8; the slices left over are shared block by block between 2, 4 or 8 queues.  A queue holds its
+ * whole slices in groups of two, one group after the other, then its part of the shared slices;
+ * within a group the units holding at least an eighth of the largest possible work come first, by
  * falling work, then the lighter ones by falling octave of work.  workspace as for the pass
  * (FM_PASS_FWD for the forward, FM_PASS_BWD otherwise); the records are copied out of it on the
  * stream.  N here is rounded up to a multiple of 128 (T counts blocks of the padded length).

@@ -9,7 +9,10 @@ constexpr int FM_QUEUES = 8;
 // Slices (batch row, head) of a queue that are ranked together, longest first; a queue works its
 // groups off one after the other.
 constexpr int FM_QUEUE_CHUNK = 2;
-inline int fm_order_slots(int units) { return ((units + FM_QUEUES - 1) / FM_QUEUES) * FM_QUEUES; }
+// Slots of a pass's queues: FM_QUEUES x the longest queue.  Slices that do not fill a round of
+// 8 queues are shared between 2, 4 or 8 queues block by block, which can make a queue up to 3 units
+// longer than an eighth of all units.
+inline int fm_order_slots(int units) { return ((units + FM_QUEUES - 1) / FM_QUEUES + 3) * FM_QUEUES; }
 // Bytes of a pass's queue area: one 16-byte record per slot, then the FM_QUEUES queue counters.
 inline size_t fm_order_bytes(int units) { return (size_t)fm_order_slots(units) * 16 + FM_QUEUES * 4; }
 // Raise a tile-loop kernel's dynamic LDS limit once per device (the attribute belongs to the device's

@@ -161,42 +161,62 @@ __global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ m
 // the slots.  Workgroups of 1024 threads.
 constexpr int kLevels = 512;
 constexpr int kGroups = FM_QUEUES;
-// workgroups of the queue-building launch: one per FM_QUEUE_CHUNK slices of every queue when slices go to
-// queues whole, else one
+// Queue of block i of slice s (slices = batch rows x heads, numbered batch-major).  Slices go to
+// queues whole, slice s to queue s % 8, as long as they fill rounds of 8; the r < 8 slices left over
+// (all slices if there are fewer than 8) are shared block by block: four of them between 2 queues
+// each, two between 4 queues each, one between all 8 (r = 4a + 2b + c), which keeps the queues
+// equally long and every slice in as few L2s as that allows.
+__host__ __device__ inline int fm_queue_of(int s, int i, int whole, int r) {
+  if (s < whole) return s % FM_QUEUES;
+  int j = s - whole;
+  if (r & 4) {
+    if (j < 4) return 2 * j + (i & 1);
+    j -= 4;
+  }
+  if (r & 2) {
+    if (j < 2) return 4 * j + (i & 3);
+    j -= 2;
+  }
+  return i & 7;
+}
+// Workgroups of the queue-building launch: one per FM_QUEUE_CHUNK whole slices of every queue, and one
+// for the slices left over, the unused slots and the queue counters.
 static inline int fm_order_grid(int B, int H) {
-  return (B * H) % FM_QUEUES == 0 ? ((B * H) / FM_QUEUES + FM_QUEUE_CHUNK - 1) / FM_QUEUE_CHUNK : 1;
+  return ((B * H) / FM_QUEUES + FM_QUEUE_CHUNK - 1) / FM_QUEUE_CHUNK + 1;
 }
 
 // work and range are indexed [batch row][block]; a unit is (batch row, head, block).
-// When batch * heads is a multiple of the queue count, slice (batch row, head) number s goes to queue
-// s % 8 whole, and a queue holds its slices in groups of FM_QUEUE_CHUNK, one group after the other:
-// the units that run at the same time then belong to few slices and share their K/V (or Q/dO) in the
-// XCD's L2 and in the memory-side cache.  (Ranking a queue's units of ALL slices by work alone spreads
-// the resident workgroups over as many slices as the queue has; with 64 slices per queue the loops
-// then stream from HBM and lose a quarter of their rate.)  Workgroup x of this launch sorts group x of
-// every queue.  Otherwise one workgroup deals all units round-robin.  Within a group (or the whole
-// set) units are ranked as key_of() describes.
+// A queue holds its whole slices in groups of FM_QUEUE_CHUNK, one group after the other, and the
+// shared slices last: the units that run at the same time then belong to few slices and share their
+// K/V (or Q/dO) in the XCD's L2 and in the memory-side cache.  (Ranking a queue's units of ALL slices
+// by work alone spreads the resident workgroups over as many slices as the queue has; with 64 slices
+// per queue the loops then stream from HBM and lose a quarter of their rate.)  Workgroup x of this
+// launch sorts group x of every queue, the last workgroup the shared slices.  Within a group units
+// are ranked as key_of() describes.
 __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ work, const int* __restrict__ range,
                                                      int batch, int heads, int units_per_bh, int max_work, int slots,
                                                      i32x4* __restrict__ order, int* __restrict__ counters) {
   __shared__ int hist[kGroups * kLevels];
   __shared__ int wave_sum[16];
   const int tid = threadIdx.x;
-  const int total_units = batch * heads * units_per_bh;
-  const bool by_head = ((batch * heads) % kGroups) == 0;
+  const int slices = batch * heads;
+  const int total_units = slices * units_per_bh;
+  const int whole = (slices / kGroups) * kGroups, left = slices - whole;
+  const bool tail = blockIdx.x == gridDim.x - 1;
   constexpr int chunk = FM_QUEUE_CHUNK;
-  const int u_begin = by_head ? blockIdx.x * chunk * kGroups * units_per_bh : 0;
-  const int u_end = by_head ? min(u_begin + chunk * kGroups * units_per_bh, total_units) : total_units;
-  const int pos_base = by_head ? blockIdx.x * chunk * units_per_bh : 0;   // first queue position of this workgroup's units
+  const int u_begin = tail ? whole * units_per_bh : blockIdx.x * chunk * kGroups * units_per_bh;
+  const int u_end = tail ? total_units : min(u_begin + chunk * kGroups * units_per_bh, whole * units_per_bh);
+  // first queue position of this workgroup's units
+  const int pos_base = tail ? (whole / kGroups) * units_per_bh : blockIdx.x * chunk * units_per_bh;
   for (int w = tid; w < kGroups * kLevels; w += 1024) hist[w] = 0;
-  if (blockIdx.x == 0) {
-    // by head every queue is filled exactly to total_units / 8; dealt round-robin the last row may have holes
-    for (int s = (by_head ? total_units : 0) + tid; s < slots; s += 1024) order[s] = i32x4{-1, 0, 0, 0};
+  if (tail) {
+    // the queue positions behind the whole slices: filled below as far as there are shared slices
+    for (int s = pos_base * kGroups + tid; s < slots; s += 1024) order[s] = i32x4{-1, 0, 0, 0};
     if (tid < kGroups) counters[tid] = 0;
   }
   __syncthreads();
   auto key_of = [&](int u) {
-    const int g = by_head ? (u / units_per_bh) % kGroups : u % kGroups;
+    const int g = fm_queue_of(u / units_per_bh, u % units_per_bh, whole, left);
     const int ru = (u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh;
     const int w_u = work[ru], mw = max_work > 0 ? max_work : 1;
     // Heavy units (an eighth of the largest possible work or more) are ranked finely by work: their

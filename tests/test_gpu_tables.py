@@ -73,22 +73,32 @@ def _check_unit_queues(w, pass_id):
     bh, blk = u // T, u % T
     b = bh // w.H
     assert np.array_equal(rec[slot, 1], lo_ref[b, blk]) and np.array_equal(rec[slot, 2], hi_ref[b, blk])
-    if (w.B * w.H) % 8 == 0:
-        assert np.array_equal(slot % 8, bh % 8), "a head's units share one queue"
+    # Queue of every unit: slices (batch row, head) go to queues whole, slice s to queue s % 8, while they
+    # fill rounds of 8; the r slices left over are shared block by block, four of them between 2 queues
+    # each, two between 4 queues each, one between all 8 (r = 4a + 2b + c).
+    slices = w.B * w.H
+    whole, r = slices // 8 * 8, slices % 8
+    j = bh - whole
+    in4 = (r & 4 != 0) & (j < 4)
+    j2 = j - (4 if r & 4 else 0)
+    in2 = ~in4 & (r & 2 != 0) & (j2 >= 0) & (j2 < 2)
+    shared_q = np.where(in4, 2 * j + (blk & 1), np.where(in2, 4 * j2 + (blk & 3), blk & 7))
+    assert np.array_equal(slot % 8, np.where(bh < whole, bh % 8, shared_q)), "queue of every unit"
     max_work = w.N // (bc if rows else br)
-    by_slice = (w.B * w.H) % 8 == 0
-    chunk = 2                      # slices of a queue that are ranked together (FM_QUEUE_CHUNK)
+    chunk = 2                      # whole slices of a queue that are ranked together (FM_QUEUE_CHUNK)
+    n_groups = -(-(whole // 8) // chunk)
+    group = np.where(bh < whole, (bh // 8) // chunk, n_groups)     # the shared slices form the last group
     for q in range(8):
         in_q = slot % 8 == q
         pos = slot[in_q] // 8
         order_q = np.argsort(pos)
-        pos, work_q, bh_q = pos[order_q], work_ref[b[in_q], blk[in_q]][order_q], bh[in_q][order_q]
-        # a queue holds its slices in groups of `chunk`, one group after the other; ranking is per group
-        seg = pos // (chunk * T) if by_slice else np.zeros_like(pos)
-        if by_slice:
-            assert np.array_equal(seg, (bh_q // 8) // chunk), "a queue's slices in groups, one group after the other"
-        for sg in np.unique(seg):
-            work = work_q[seg == sg]
+        pos, work_q, group_q = pos[order_q], work_ref[b[in_q], blk[in_q]][order_q], group[in_q][order_q]
+        assert np.array_equal(pos, np.arange(pos.size)), "a queue has no holes"
+        assert np.all(np.diff(group_q) >= 0), "a queue's groups of slices, one after the other"
+        whole_q = group_q < n_groups
+        assert np.array_equal(pos[whole_q] // (chunk * T), group_q[whole_q])
+        for sg in np.unique(group_q):
+            work = work_q[group_q == sg]
             heavy = work * 8 >= max_work
             if heavy.any():
                 assert not heavy[np.argmin(heavy):].any() or heavy.all(), "heavy units come first"
@@ -117,10 +127,13 @@ def test_unit_queues_small_families(kind):
         _check_unit_queues(w, p)
 
 
-@pytest.mark.parametrize("B,H", [(5, 8), (3, 16), (1, 8)])
-def test_unit_queues_many_slices(B, H):
-    """Slice counts that give a queue several groups of slices, the last one partial."""
+@pytest.mark.parametrize("B,H,N", [(5, 8, 2048), (3, 16, 2048), (1, 8, 2048), (1, 1, 1152), (1, 2, 1152), (3, 1, 1152),
+                                   (1, 4, 1152), (5, 1, 1152), (2, 3, 1152), (1, 7, 1152), (3, 5, 1152), (1, 12, 2048),
+                                   (23, 1, 384), (3, 20, 640)])
+def test_unit_queues_many_slices(B, H, N):
+    """Slice counts that give a queue several groups of whole slices (the last one partial) and every
+    number of shared slices, with block counts that do not divide by the sharing."""
     import paper_2410_01359_amd as fm
-    w = workloads.small_workload("causal_document", 2048, seed=13, B=B, H=H, d=128)
+    w = workloads.small_workload("causal_document", N, seed=13, B=B, H=H, d=128)
     for p in (fm.FM_PASS_FWD, fm.FM_PASS_BWD_DQ, fm.FM_PASS_BWD_DKDV):
         _check_unit_queues(w, p)
