@@ -301,15 +301,11 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* out
     a.sq = a.so = a.sdo = a.sdq = dense(H, N, d);
     a.sk = a.sv = a.sdk = a.sdv = dense(Hk, N, d);
   }
-  e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_DQ_BC, (int*)(ws + sq.minmax), stream);
-  if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_row_order(a.minmax_dq, B, H, Np, FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.work), (int*)(ws + sq.range),
-                          (int*)(ws + sq.order), stream);
-  if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_DKDV_BC, (int*)(ws + skv.minmax), stream);
-  if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_col_order(a.minmax_dkdv, B, Hk, Np, FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.work),
-                          (int*)(ws + skv.range), (int*)(ws + skv.order), stream);
+  const FmSetup rows{FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.minmax), (int*)(ws + sq.work), (int*)(ws + sq.range),
+                     (int*)(ws + sq.order)};
+  const FmSetup cols{FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.minmax), (int*)(ws + skv.work), (int*)(ws + skv.range),
+                     (int*)(ws + skv.order)};
+  e = fm_launch_bwd_setup(lts, lte, uts, ute, B, H, Hk, Np, rows, cols, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
   e = fm_launch_dvec(a, stream);

@@ -37,6 +37,18 @@ constexpr int FM_FWD_BR = 128, FM_FWD_BC = 64;
 constexpr int FM_DQ_BR = 128, FM_DQ_BC = 64;
 constexpr int FM_DKDV_BR = 64, FM_DKDV_BC = 128;
 
+// One pass's setup buffers (in the workspace) and tile shape.
+struct FmSetup {
+  int block_r, block_c;
+  int* minmax;
+  int* work;
+  int* range;
+  int* order;
+};
+// The backward's whole setup (tables, work pre-passes and unit queues of the dQ pass `rows` and of the
+// dK/dV pass `cols`, whose units count K/V heads) in three launches.
+hipError_t fm_launch_bwd_setup(const int* lts, const int* lte, const int* uts, const int* ute, int B, int H, int Hk,
+                               int N, const FmSetup& rows, const FmSetup& cols, hipStream_t stream);
 hipError_t fm_launch_preprocess(const int* lts, const int* lte, const int* uts, const int* ute, int B, int N,
                                 int block_c, int* minmax, hipStream_t stream);
 // Padded copies of the four bound vectors: [4][B][Np], columns >= N masked for every row.

@@ -10,12 +10,12 @@ namespace fm {
 
 // One wave per (batch row, key block).  Lanes stride over the block's columns,
 // then a butterfly over the 64 lanes leaves the 8 results in every lane.
-__global__ __launch_bounds__(256) void preprocess_kernel(const int* __restrict__ lts, const int* __restrict__ lte,
-                                                         const int* __restrict__ uts, const int* __restrict__ ute,
-                                                         int n, int block_c, int t_c, int total_blocks,
-                                                         int* __restrict__ minmax) {
+__device__ __forceinline__ void preprocess_body(const int* __restrict__ lts, const int* __restrict__ lte,
+                                                const int* __restrict__ uts, const int* __restrict__ ute, int n,
+                                                int block_c, int t_c, int total_blocks, int* __restrict__ minmax,
+                                                int block) {
   const int lane = threadIdx.x & 63;
-  const int blk = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int blk = block * 4 + (threadIdx.x >> 6);
   if (blk >= total_blocks) return;
   const int b = blk / t_c, j = blk - b * t_c;
   const int c0 = j * block_c;
@@ -53,6 +53,26 @@ __global__ __launch_bounds__(256) void preprocess_kernel(const int* __restrict__
   }
 }
 
+__global__ __launch_bounds__(256) void preprocess_kernel(const int* __restrict__ lts, const int* __restrict__ lte,
+                                                         const int* __restrict__ uts, const int* __restrict__ ute,
+                                                         int n, int block_c, int t_c, int total_blocks,
+                                                         int* __restrict__ minmax) {
+  preprocess_body(lts, lte, uts, ute, n, block_c, t_c, total_blocks, minmax, blockIdx.x);
+}
+
+// The tables of two block widths in one launch (the backward's two loops tile the keys differently):
+// workgroups [0, blocks_a) build table a, the rest table b.
+__global__ __launch_bounds__(256) void preprocess2_kernel(const int* __restrict__ lts, const int* __restrict__ lte,
+                                                          const int* __restrict__ uts, const int* __restrict__ ute,
+                                                          int n, int batch, int block_c_a, int* __restrict__ minmax_a,
+                                                          int blocks_a, int block_c_b, int* __restrict__ minmax_b) {
+  const bool first = (int)blockIdx.x < blocks_a;
+  const int block_c = first ? block_c_a : block_c_b;
+  const int t_c = (n + block_c - 1) / block_c;
+  preprocess_body(lts, lte, uts, ute, n, block_c, t_c, batch * t_c, first ? minmax_a : minmax_b,
+                  first ? blockIdx.x : blockIdx.x - blocks_a);
+}
+
 __global__ __launch_bounds__(256) void classify_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
                                                        int t_c, uint8_t* __restrict__ cls) {
   const int b = blockIdx.z, i = blockIdx.y;
@@ -84,11 +104,11 @@ __global__ __launch_bounds__(256) void pad_bounds_kernel(const int* __restrict__
 // Work of one row block = number of key blocks that are not fully masked, and
 // the range of key blocks that contains them (the tile loops only scan that).
 // One wave per (batch row, row block); lanes stride over the key blocks.
-__global__ __launch_bounds__(256) void row_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
-                                                       int t_c, int total_units, int* __restrict__ work,
-                                                       int* __restrict__ range) {
+__device__ __forceinline__ void row_work_body(const int* __restrict__ minmax, int n, int block_r, int t_r, int t_c,
+                                              int total_units, int* __restrict__ work, int* __restrict__ range,
+                                              int block) {
   const int lane = threadIdx.x & 63;
-  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int u = block * 4 + (threadIdx.x >> 6);
   if (u >= total_units) return;
   const int b = u / t_r, i = u - b * t_r;
   const int r0 = i * block_r, r1 = min(r0 + block_r, n);
@@ -113,12 +133,18 @@ __global__ __launch_bounds__(256) void row_work_kernel(const int* __restrict__ m
   }
 }
 
-// Work of one key block = number of row blocks that are not fully masked.
-__global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
+__global__ __launch_bounds__(256) void row_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
                                                        int t_c, int total_units, int* __restrict__ work,
                                                        int* __restrict__ range) {
+  row_work_body(minmax, n, block_r, t_r, t_c, total_units, work, range, blockIdx.x);
+}
+
+// Work of one key block = number of row blocks that are not fully masked.
+__device__ __forceinline__ void col_work_body(const int* __restrict__ minmax, int n, int block_r, int t_r, int t_c,
+                                              int total_units, int* __restrict__ work, int* __restrict__ range,
+                                              int block) {
   const int lane = threadIdx.x & 63;
-  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int u = block * 4 + (threadIdx.x >> 6);
   if (u >= total_units) return;
   const int b = u / t_c, j = u - b * t_c;
   const MinMax8 t = load_minmax(minmax + (size_t)b * 8 * t_c, t_c, j);
@@ -142,6 +168,28 @@ __global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ m
     range[2 * u] = cnt ? lo : 0;
     range[2 * u + 1] = hi;
   }
+}
+
+__global__ __launch_bounds__(256) void col_work_kernel(const int* __restrict__ minmax, int n, int block_r, int t_r,
+                                                       int t_c, int total_units, int* __restrict__ work,
+                                                       int* __restrict__ range) {
+  col_work_body(minmax, n, block_r, t_r, t_c, total_units, work, range, blockIdx.x);
+}
+
+// One pass's work pre-pass as arguments, so that the backward can run both of its passes' in one launch.
+struct WorkJob {
+  const int* minmax;
+  int block_r, t_r, t_c, total_units;
+  int* work;
+  int* range;
+};
+// workgroups [0, blocks_rows) count per row block (job `rows`), the rest per key block (job `cols`)
+__global__ __launch_bounds__(256) void work2_kernel(WorkJob rows, int blocks_rows, WorkJob cols, int n) {
+  if ((int)blockIdx.x < blocks_rows)
+    row_work_body(rows.minmax, n, rows.block_r, rows.t_r, rows.t_c, rows.total_units, rows.work, rows.range, blockIdx.x);
+  else
+    col_work_body(cols.minmax, n, cols.block_r, cols.t_r, cols.t_c, cols.total_units, cols.work, cols.range,
+                  blockIdx.x - blocks_rows);
 }
 
 // Unit queues (the tile scheduler).  Workgroup x of a launch runs on XCD x % 8.
@@ -193,21 +241,32 @@ static inline int fm_order_grid(int B, int H) {
 // per queue the loops then stream from HBM and lose a quarter of their rate.)  Workgroup x of this
 // launch sorts group x of every queue, the last workgroup the shared slices.  Within a group units
 // are ranked as key_of() describes.
-__global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ work, const int* __restrict__ range,
-                                                     int batch, int heads, int units_per_bh, int max_work, int slots,
-                                                     i32x4* __restrict__ order, int* __restrict__ counters) {
+struct OrderJob {
+  const int* work;
+  const int* range;
+  int batch, heads, units_per_bh, max_work, slots;
+  i32x4* order;
+  int* counters;
+};
+__device__ __forceinline__ void order_body(const OrderJob& job, int block, int blocks) {
+  const int* __restrict__ work = job.work;
+  const int* __restrict__ range = job.range;
+  const int batch = job.batch, heads = job.heads, units_per_bh = job.units_per_bh, max_work = job.max_work;
+  const int slots = job.slots;
+  i32x4* __restrict__ order = job.order;
+  int* __restrict__ counters = job.counters;
   __shared__ int hist[kGroups * kLevels];
   __shared__ int wave_sum[16];
   const int tid = threadIdx.x;
   const int slices = batch * heads;
   const int total_units = slices * units_per_bh;
   const int whole = (slices / kGroups) * kGroups, left = slices - whole;
-  const bool tail = blockIdx.x == gridDim.x - 1;
+  const bool tail = block == blocks - 1;
   constexpr int chunk = FM_QUEUE_CHUNK;
-  const int u_begin = tail ? whole * units_per_bh : blockIdx.x * chunk * kGroups * units_per_bh;
+  const int u_begin = tail ? whole * units_per_bh : block * chunk * kGroups * units_per_bh;
   const int u_end = tail ? total_units : min(u_begin + chunk * kGroups * units_per_bh, whole * units_per_bh);
   // first queue position of this workgroup's units
-  const int pos_base = tail ? (whole / kGroups) * units_per_bh : blockIdx.x * chunk * units_per_bh;
+  const int pos_base = tail ? (whole / kGroups) * units_per_bh : block * chunk * units_per_bh;
   for (int w = tid; w < kGroups * kLevels; w += 1024) hist[w] = 0;
   if (tail) {
     // the queue positions behind the whole slices: filled below as far as there are shared slices
@@ -276,6 +335,16 @@ __global__ __launch_bounds__(1024) void order_kernel(const int* __restrict__ wor
   }
 }
 
+__global__ __launch_bounds__(1024) void order_kernel(OrderJob job) { order_body(job, blockIdx.x, gridDim.x); }
+
+// the queues of two passes in one launch: workgroups [0, blocks_a) build job a's, the rest job b's
+__global__ __launch_bounds__(1024) void order2_kernel(OrderJob a, int blocks_a, OrderJob b) {
+  if ((int)blockIdx.x < blocks_a)
+    order_body(a, blockIdx.x, blocks_a);
+  else
+    order_body(b, blockIdx.x - blocks_a, gridDim.x - blocks_a);
+}
+
 }  // namespace fm
 
 using namespace fm;
@@ -306,6 +375,11 @@ hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int 
   return hipGetLastError();
 }
 
+static OrderJob order_job(int* work, int* range, int B, int H, int units_per_bh, int max_work, int* order) {
+  const int slots = fm_order_slots(B * H * units_per_bh);
+  return OrderJob{work, range, B, H, units_per_bh, max_work, slots, (i32x4*)order, order + 4 * (size_t)slots};
+}
+
 hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream) {
   const int t_c = (N + block_c - 1) / block_c;
@@ -313,9 +387,8 @@ hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block
   const int total = B * t_r;
   hipLaunchKernelGGL(row_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
-  const int slots = fm_order_slots(B * H * t_r);
-  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream, work, range, B, H, t_r, t_c, slots, (i32x4*)order,
-                     order + 4 * (size_t)slots);
+  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream,
+                     order_job(work, range, B, H, t_r, t_c, order));
   return hipGetLastError();
 }
 
@@ -326,8 +399,26 @@ hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block
   const int total = B * t_c;
   hipLaunchKernelGGL(col_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
-  const int slots = fm_order_slots(B * H * t_c);
-  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream, work, range, B, H, t_c, t_r, slots, (i32x4*)order,
-                     order + 4 * (size_t)slots);
+  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream,
+                     order_job(work, range, B, H, t_c, t_r, order));
+  return hipGetLastError();
+}
+
+// The backward's setup in three launches: both min/max tables, both work pre-passes, both passes' queues.
+hipError_t fm_launch_bwd_setup(const int* lts, const int* lte, const int* uts, const int* ute, int B, int H, int Hk,
+                               int N, const FmSetup& rows, const FmSetup& cols, hipStream_t stream) {
+  const int tc_r = (N + rows.block_c - 1) / rows.block_c, tr_r = (N + rows.block_r - 1) / rows.block_r;
+  const int tc_c = (N + cols.block_c - 1) / cols.block_c, tr_c = (N + cols.block_r - 1) / cols.block_r;
+  const int pre_a = (B * tc_r + 3) / 4, pre_b = (B * tc_c + 3) / 4;
+  hipLaunchKernelGGL(preprocess2_kernel, dim3(pre_a + pre_b), dim3(256), 0, stream, lts, lte, uts, ute, N, B,
+                     rows.block_c, rows.minmax, pre_a, cols.block_c, cols.minmax);
+  const WorkJob wr{rows.minmax, rows.block_r, tr_r, tc_r, B * tr_r, rows.work, rows.range};
+  const WorkJob wc{cols.minmax, cols.block_r, tr_c, tc_c, B * tc_c, cols.work, cols.range};
+  const int work_a = (wr.total_units + 3) / 4, work_b = (wc.total_units + 3) / 4;
+  hipLaunchKernelGGL(work2_kernel, dim3(work_a + work_b), dim3(256), 0, stream, wr, work_a, wc, N);
+  const int grid_a = fm_order_grid(B, H), grid_b = fm_order_grid(B, Hk);
+  hipLaunchKernelGGL(order2_kernel, dim3(grid_a + grid_b), dim3(1024), 0, stream,
+                     order_job(rows.work, rows.range, B, H, tr_r, tc_r, rows.order), grid_a,
+                     order_job(cols.work, cols.range, B, Hk, tc_c, tr_c, cols.order));
   return hipGetLastError();
 }
