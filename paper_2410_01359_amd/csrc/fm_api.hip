@@ -171,7 +171,7 @@ static int fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
   int* order = (int*)(ws + sp.order);
   e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, FM_FWD_BC, minmax, stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = fm_launch_row_order(minmax, B, H, Np, FM_FWD_BR, FM_FWD_BC, work, range, order, stream);
+  e = fm_launch_row_order(minmax, B, H, Hk, Np, FM_FWD_BR, FM_FWD_BC, work, range, order, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
   FmFwdArgs a;
@@ -221,7 +221,7 @@ int flashmask_unit_queues(int pass, const int32_t* lts, const int32_t* lte, cons
   int* minmax = (int*)(ws + sp.minmax);
   e = fm_launch_preprocess(lts, lte, uts, ute, B, Np, bc, minmax, stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = rows ? fm_launch_row_order(minmax, B, H, Np, br, bc, (int*)(ws + sp.work), (int*)(ws + sp.range),
+  e = rows ? fm_launch_row_order(minmax, B, H, H, Np, br, bc, (int*)(ws + sp.work), (int*)(ws + sp.range),
                                  (int*)(ws + sp.order), stream)
            : fm_launch_col_order(minmax, B, H, Np, br, bc, (int*)(ws + sp.work), (int*)(ws + sp.range),
                                  (int*)(ws + sp.order), stream);

@@ -59,7 +59,7 @@ hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int 
 // work: int[B * T_r] (resp. B * T_c); range: int[2 * B * T] = first live block and one past the
 // last live block of every unit (0, 0 if none); order: fm_order_bytes(B*H*T) bytes = the slot
 // records {unit, first, last, 0} followed by the queue counters (zeroed here).
-hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
+hipError_t fm_launch_row_order(const int* minmax, int B, int H, int Hk, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream);
 hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream);

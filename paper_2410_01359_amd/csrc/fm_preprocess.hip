@@ -244,7 +244,10 @@ static inline int fm_order_grid(int B, int H) {
 struct OrderJob {
   const int* work;
   const int* range;
-  int batch, heads, units_per_bh, max_work, slots;
+  int batch, heads, units_per_bh;   // a queue slice: (batch row, head); with grouped K/V heads `heads` counts K/V
+                                    // heads and a slice holds the units of all query heads of the group
+  int blocks;                       // blocks per (batch row, query head): units_per_bh = group size x blocks
+  int max_work, slots;
   i32x4* order;
   int* counters;
 };
@@ -252,6 +255,7 @@ __device__ __forceinline__ void order_body(const OrderJob& job, int block, int b
   const int* __restrict__ work = job.work;
   const int* __restrict__ range = job.range;
   const int batch = job.batch, heads = job.heads, units_per_bh = job.units_per_bh, max_work = job.max_work;
+  const int blocks_per_head = job.blocks;
   const int slots = job.slots;
   i32x4* __restrict__ order = job.order;
   int* __restrict__ counters = job.counters;
@@ -276,7 +280,7 @@ __device__ __forceinline__ void order_body(const OrderJob& job, int block, int b
   __syncthreads();
   auto key_of = [&](int u) {
     const int g = fm_queue_of(u / units_per_bh, u % units_per_bh, whole, left);
-    const int ru = (u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh;
+    const int ru = (u / (heads * units_per_bh)) * blocks_per_head + u % blocks_per_head;
     const int w_u = work[ru], mw = max_work > 0 ? max_work : 1;
     // Heavy units (an eighth of the largest possible work or more) are ranked finely by work: their
     // order decides how evenly the queue ends.  Lighter ones are ranked by octave of work and, within
@@ -330,7 +334,7 @@ __device__ __forceinline__ void order_body(const OrderJob& job, int block, int b
     const int g = key / kLevels;
     const int pos = pos_base + atomicAdd(&hist[key], 1) - group_start[g];
     const int slot = pos * kGroups + g;
-    const int ru = (u / (heads * units_per_bh)) * units_per_bh + u % units_per_bh;
+    const int ru = (u / (heads * units_per_bh)) * blocks_per_head + u % blocks_per_head;
     if (slot < slots) order[slot] = i32x4{u, range[2 * ru], range[2 * ru + 1], 0};
   }
 }
@@ -375,20 +379,23 @@ hipError_t fm_launch_classify(const int* minmax, int B, int N, int block_r, int 
   return hipGetLastError();
 }
 
-static OrderJob order_job(int* work, int* range, int B, int H, int units_per_bh, int max_work, int* order) {
-  const int slots = fm_order_slots(B * H * units_per_bh);
-  return OrderJob{work, range, B, H, units_per_bh, max_work, slots, (i32x4*)order, order + 4 * (size_t)slots};
+// H heads per batch row in groups of `group` that share a K/V head (1: no sharing): the heads of a group
+// form one queue slice, so that they run on the XCD whose L2 holds their K/V.
+static OrderJob order_job(int* work, int* range, int B, int H, int group, int blocks, int max_work, int* order) {
+  const int slots = fm_order_slots(B * H * blocks);
+  return OrderJob{work, range, B, H / group, group * blocks, blocks, max_work, slots, (i32x4*)order,
+                  order + 4 * (size_t)slots};
 }
 
-hipError_t fm_launch_row_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
+hipError_t fm_launch_row_order(const int* minmax, int B, int H, int Hk, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream) {
   const int t_c = (N + block_c - 1) / block_c;
   const int t_r = (N + block_r - 1) / block_r;
   const int total = B * t_r;
   hipLaunchKernelGGL(row_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
-  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream,
-                     order_job(work, range, B, H, t_r, t_c, order));
+  hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, Hk)), dim3(1024), 0, stream,
+                     order_job(work, range, B, H, H / Hk, t_r, t_c, order));
   return hipGetLastError();
 }
 
@@ -400,7 +407,7 @@ hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block
   hipLaunchKernelGGL(col_work_kernel, dim3((total + 3) / 4), dim3(256), 0, stream, minmax, N, block_r, t_r, t_c, total,
                      work, range);
   hipLaunchKernelGGL(order_kernel, dim3(fm_order_grid(B, H)), dim3(1024), 0, stream,
-                     order_job(work, range, B, H, t_c, t_r, order));
+                     order_job(work, range, B, H, 1, t_c, t_r, order));
   return hipGetLastError();
 }
 
@@ -416,9 +423,9 @@ hipError_t fm_launch_bwd_setup(const int* lts, const int* lte, const int* uts, c
   const WorkJob wc{cols.minmax, cols.block_r, tr_c, tc_c, B * tc_c, cols.work, cols.range};
   const int work_a = (wr.total_units + 3) / 4, work_b = (wc.total_units + 3) / 4;
   hipLaunchKernelGGL(work2_kernel, dim3(work_a + work_b), dim3(256), 0, stream, wr, work_a, wc, N);
-  const int grid_a = fm_order_grid(B, H), grid_b = fm_order_grid(B, Hk);
+  const int grid_a = fm_order_grid(B, Hk), grid_b = fm_order_grid(B, Hk);
   hipLaunchKernelGGL(order2_kernel, dim3(grid_a + grid_b), dim3(1024), 0, stream,
-                     order_job(rows.work, rows.range, B, H, tr_r, tc_r, rows.order), grid_a,
-                     order_job(cols.work, cols.range, B, Hk, tc_c, tr_c, cols.order));
+                     order_job(rows.work, rows.range, B, H, H / Hk, tr_r, tc_r, rows.order), grid_a,
+                     order_job(cols.work, cols.range, B, Hk, 1, tc_c, tr_c, cols.order));
   return hipGetLastError();
 }
