@@ -114,6 +114,7 @@ __device__ __forceinline__ void row_work_body(const int* __restrict__ minmax, in
   const int r0 = i * block_r, r1 = min(r0 + block_r, n);
   const int* table = minmax + (size_t)b * 8 * t_c;
   int cnt = 0, lo = t_c, hi = 0;
+#pragma unroll 8   // the table loads of several iterations in flight: the scan is bound by their latency
   for (int j = lane; j < t_c; j += 64)
     if (classify_tile(r0, r1, load_minmax(table, t_c, j)) != T_FULLY) {
       ++cnt;
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(256) void work2_kernel(WorkJob rows, int blocks_row
 // A slot is the record {unit, first live block, one past the last live block, 0},
 // so a workgroup learns all it needs to start from one 16-byte load; slots with
 // no unit hold unit = -1.  The kernel also zeroes the 8 queue counters behind
-// the slots.  Workgroups of 1024 threads.
+// the slots.
 constexpr int kLevels = 512;
 constexpr int kGroups = FM_QUEUES;
 // Queue of block i of slice s (slices = batch rows x heads, numbered batch-major).  Slices go to
@@ -227,10 +228,10 @@ __host__ __device__ inline int fm_queue_of(int s, int i, int whole, int r) {
   }
   return i & 7;
 }
-// Workgroups of the queue-building launch: one per FM_QUEUE_CHUNK whole slices of every queue, and one
-// for the slices left over, the unused slots and the queue counters.
+// Workgroups of the queue-building launch: per queue, one for every FM_QUEUE_CHUNK whole slices and one
+// for its part of the slices left over, its unused slots and its counter.
 static inline int fm_order_grid(int B, int H) {
-  return ((B * H) / FM_QUEUES + FM_QUEUE_CHUNK - 1) / FM_QUEUE_CHUNK + 1;
+  return FM_QUEUES * (((B * H) / FM_QUEUES + FM_QUEUE_CHUNK - 1) / FM_QUEUE_CHUNK + 1);
 }
 
 // work and range are indexed [batch row][block]; a unit is (batch row, head, block).
@@ -238,9 +239,8 @@ static inline int fm_order_grid(int B, int H) {
 // shared slices last: the units that run at the same time then belong to few slices and share their
 // K/V (or Q/dO) in the XCD's L2 and in the memory-side cache.  (Ranking a queue's units of ALL slices
 // by work alone spreads the resident workgroups over as many slices as the queue has; with 64 slices
-// per queue the loops then stream from HBM and lose a quarter of their rate.)  Workgroup x of this
-// launch sorts group x of every queue, the last workgroup the shared slices.  Within a group units
-// are ranked as key_of() describes.
+// per queue the loops then stream from HBM and lose a quarter of their rate.)  One workgroup of the
+// launch sorts one group of one queue.  Within a group units are ranked as rank_of() describes.
 struct OrderJob {
   const int* work;
   const int* range;
@@ -251,35 +251,44 @@ struct OrderJob {
   i32x4* order;
   int* counters;
 };
+// Workgroup `block` of `blocks` = 8 x (groups of whole slices + 1): block % 8 is the queue, block / 8 the
+// group; the last group is the shared slices, whose workgroups also clear their queue's unused slots
+// and counter.
 __device__ __forceinline__ void order_body(const OrderJob& job, int block, int blocks) {
   const int* __restrict__ work = job.work;
   const int* __restrict__ range = job.range;
-  const int batch = job.batch, heads = job.heads, units_per_bh = job.units_per_bh, max_work = job.max_work;
+  const int heads = job.heads, units_per_bh = job.units_per_bh, max_work = job.max_work;
   const int blocks_per_head = job.blocks;
   const int slots = job.slots;
   i32x4* __restrict__ order = job.order;
-  int* __restrict__ counters = job.counters;
-  __shared__ int hist[kGroups * kLevels];
+  __shared__ int hist[kLevels];
   __shared__ int wave_sum[16];
   const int tid = threadIdx.x;
-  const int slices = batch * heads;
-  const int total_units = slices * units_per_bh;
+  const int slices = job.batch * heads;
   const int whole = (slices / kGroups) * kGroups, left = slices - whole;
-  const bool tail = block == blocks - 1;
+  const int g = block % kGroups, grp = block / kGroups;
+  const bool tail = grp == blocks / kGroups - 1;
   constexpr int chunk = FM_QUEUE_CHUNK;
-  const int u_begin = tail ? whole * units_per_bh : block * chunk * kGroups * units_per_bh;
-  const int u_end = tail ? total_units : min(u_begin + chunk * kGroups * units_per_bh, whole * units_per_bh);
-  // first queue position of this workgroup's units
-  const int pos_base = tail ? (whole / kGroups) * units_per_bh : block * chunk * units_per_bh;
-  for (int w = tid; w < kGroups * kLevels; w += 1024) hist[w] = 0;
+  // Candidates of this workgroup: the units of its queue's whole slices of the group (slice numbers
+  // (grp * chunk + c) * 8 + g), or every unit of the shared slices, of which it keeps its queue's.
+  const int first_slice = tail ? whole : (grp * chunk) * kGroups + g;
+  const int n_slices = tail ? left : min(chunk, (whole - first_slice + kGroups - 1) / kGroups);
+  const int candidates = n_slices * units_per_bh;
+  const int pos_base = tail ? (whole / kGroups) * units_per_bh : grp * chunk * units_per_bh;
+  auto unit_at = [&](int idx) {   // unit number of candidate idx, or -1 if it belongs to another queue
+    const int c = idx / units_per_bh, i = idx - c * units_per_bh;
+    const int slice = tail ? first_slice + c : first_slice + c * kGroups;
+    if (tail && fm_queue_of(slice, i, whole, left) != g) return -1;
+    return slice * units_per_bh + i;
+  };
+  if (tid < kLevels) hist[tid] = 0;
   if (tail) {
-    // the queue positions behind the whole slices: filled below as far as there are shared slices
-    for (int s = pos_base * kGroups + tid; s < slots; s += 1024) order[s] = i32x4{-1, 0, 0, 0};
-    if (tid < kGroups) counters[tid] = 0;
+    // this queue's positions behind the whole slices: filled below as far as there are shared slices
+    for (int p = pos_base + tid; p * kGroups + g < slots; p += 1024) order[p * kGroups + g] = i32x4{-1, 0, 0, 0};
+    if (tid == 0) job.counters[g] = 0;
   }
   __syncthreads();
-  auto key_of = [&](int u) {
-    const int g = fm_queue_of(u / units_per_bh, u % units_per_bh, whole, left);
+  auto rank_of = [&](int u) {
     const int ru = (u / (heads * units_per_bh)) * blocks_per_head + u % blocks_per_head;
     const int w_u = work[ru], mw = max_work > 0 ? max_work : 1;
     // Heavy units (an eighth of the largest possible work or more) are ranked finely by work: their
@@ -297,18 +306,16 @@ __device__ __forceinline__ void order_body(const OrderJob& job, int block, int b
       const int pos = min((int)(((long long)range[2 * ru] * kPos) / mw), kPos - 1);
       rank = kFine + oct * kPos + pos;
     }
-    return g * kLevels + rank;
+    return rank;
   };
-  for (int u = u_begin + tid; u < u_end; u += 1024) atomicAdd(&hist[key_of(u)], 1);
-  __syncthreads();
-  // exclusive scan of hist (4096 entries, 4 per thread)
-  int v[4], sum = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    v[e] = hist[tid * 4 + e];
-    sum += v[e];
+  for (int idx = tid; idx < candidates; idx += 1024) {
+    const int u = unit_at(idx);
+    if (u >= 0) atomicAdd(&hist[rank_of(u)], 1);
   }
-  int incl = sum;
+  __syncthreads();
+  // exclusive scan of hist (512 entries, one per thread of the first 8 waves)
+  const int v = tid < kLevels ? hist[tid] : 0;
+  int incl = v;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int y = __shfl_up(incl, off, 64);
@@ -318,21 +325,13 @@ __device__ __forceinline__ void order_body(const OrderJob& job, int block, int b
   __syncthreads();
   int base = 0;
   for (int w = 0; w < (tid >> 6); ++w) base += wave_sum[w];
-  int run = base + incl - sum;
   __syncthreads();
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    hist[tid * 4 + e] = run;  // start offset of this key in the concatenated sorted lists
-    run += v[e];
-  }
+  if (tid < kLevels) hist[tid] = base + incl - v;   // first queue position (within the group) of this rank
   __syncthreads();
-  __shared__ int group_start[kGroups];
-  if (tid < kGroups) group_start[tid] = hist[tid * kLevels];
-  __syncthreads();
-  for (int u = u_begin + tid; u < u_end; u += 1024) {
-    const int key = key_of(u);
-    const int g = key / kLevels;
-    const int pos = pos_base + atomicAdd(&hist[key], 1) - group_start[g];
+  for (int idx = tid; idx < candidates; idx += 1024) {
+    const int u = unit_at(idx);
+    if (u < 0) continue;
+    const int pos = pos_base + atomicAdd(&hist[rank_of(u)], 1);
     const int slot = pos * kGroups + g;
     const int ru = (u / (heads * units_per_bh)) * blocks_per_head + u % blocks_per_head;
     if (slot < slots) order[slot] = i32x4{u, range[2 * ru], range[2 * ru + 1], 0};
