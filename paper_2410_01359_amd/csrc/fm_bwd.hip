@@ -325,7 +325,7 @@ struct DkdvCfg {
   static constexpr int STAGE = Q_BYTES + DO_BYTES + VEC_BYTES;
   static constexpr int LIST_CAP = 2048;
   static constexpr int CNT_OFF = LIST_CAP * 4;
-  static constexpr int STAGE_OFF = CNT_OFF + 64;
+  static constexpr int STAGE_OFF = CNT_OFF + 256;   // stages start at multiples of 256 bytes (dkdv_operand)
   // One workgroup per CU: a tile's math takes about a microsecond, less than a
   // trip to L2/HBM, so tiles are copied three steps ahead into a ring of four.
   static constexpr int NSTAGE = 4;
@@ -435,22 +435,40 @@ __device__ __forceinline__ constexpr int dkdv_kk(int y) {
   return H + (y - 3 * H);
 }
 
-// LDS operand of step x of the tile whose Q tile starts at qs (dO tile right behind it)
+// Per-lane LDS addresses of a list entry's stage: the stage's address plus the lane-dependent part of
+// the three read patterns (row reads; transpose reads of rows 0-7 and 8-15 of a 16-row group).  A
+// step's column offset is XORed into the sum -- stage addresses are multiples of 256 bytes, so the sum
+// keeps the lane part's low byte -- which costs one instruction per read and no register that lives
+// across tiles; XORing into the lane part first would either keep every (pattern, column) pair in a
+// register for the whole loop or take two instructions per read.
+struct DkdvBases {
+  unsigned a, t0, t1;
+};
+__device__ __forceinline__ DkdvBases dkdv_bases(const char* qs, int a_base, int t_base0, int t_base1) {
+  const unsigned s = lds_address(qs);
+  return DkdvBases{s + (unsigned)a_base, s + (unsigned)t_base0, s + (unsigned)t_base1};
+}
+__device__ __forceinline__ bf16x8 lds_read_row16(unsigned addr) { return *(FM_LDS const bf16x8*)(size_t)addr; }
+__device__ __forceinline__ bf16x4 lds_read_tr16_at(unsigned addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FM_LDS bf16x4*)(size_t)addr);
+}
+
+// LDS operand of step x of the list entry whose stage addresses are bs (Q tile, dO tile right behind it)
 template <int D>
-__device__ __forceinline__ bf16x8 dkdv_operand(const char* qs, int x, int a_base, int t_base0, int t_base1) {
+__device__ __forceinline__ bf16x8 dkdv_operand(const DkdvBases& bs, int x) {
   using L = TileLayout<D>;
   constexpr int NKK = D / 16, NDB = D / 32, NST = 2 * NKK;
-  const char* dos = qs + DkdvCfg<D>::Q_BYTES;
+  constexpr unsigned DO = DkdvCfg<D>::Q_BYTES;
+  static_assert(DkdvCfg<D>::STAGE % 256 == 0 && DkdvCfg<D>::STAGE_OFF % 256 == 0 && DO % 256 == 0, "XOR after add");
   if (x < 2 * NST) {             // row reads: Q or dO rows of block x / NST as MFMA A operand
     const int qb = x / NST;
-    const char* tile = dkdv_is_s<D>(x % NST) ? qs : dos;
-    return *(const bf16x8*)(tile + qb * 32 * L::RS + L::add_col(a_base, dkdv_kk<D>(x % NST) * 32));
+    const unsigned tile = dkdv_is_s<D>(x % NST) ? 0u : DO;
+    return lds_read_row16((bs.a ^ (unsigned)(dkdv_kk<D>(x % NST) * 32)) + tile + qb * 32 * L::RS);
   }
   // transpose reads: dO (even step, dV) or Q (odd step, dK) as MFMA B operand
   const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
-  const char* tile = (u & 1) ? qs : dos;
-  const char* rowp = tile + (qb * 32 + 16 * h) * L::RS;
-  return cat4(lds_read_tr16(rowp + L::add_col(t_base0, db * 64)), lds_read_tr16(rowp + L::add_col(t_base1, db * 64)));
+  const unsigned rows = ((u & 1) ? 0u : DO) + (qb * 32 + 16 * h) * L::RS;
+  return cat4(lds_read_tr16_at((bs.t0 ^ (unsigned)(db * 64)) + rows), lds_read_tr16_at((bs.t1 ^ (unsigned)(db * 64)) + rows));
 }
 
 // The workgroup-level step that every wave takes once per list entry, in the middle of the
@@ -490,6 +508,8 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
   constexpr int XS = NX - (C::NC > RD ? C::NC : RD);   // step of the workgroup sync; the copies follow one per step
   static_assert(NX % RD == 0 && XS > 0, "ring layout");
   const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  const DkdvBases bs_cur = dkdv_bases(qs, a_base, t_base0, t_base1);
+  const DkdvBases bs_next = dkdv_bases(ah.nqs, a_base, t_base0, t_base1);
 
   f32x16 sb[2], pb[2];             // S then P, dP then dS, of the two blocks
   bf16x8 pa[2][2], dsa[2][2];      // bf16 P^T and dS^T, [block][16-row half]
@@ -525,9 +545,9 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
     } else {
       const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
       if (u & 1)
-        dkacc[db] = mfma32(dsa[qb][h], op[x % RD], dkacc[db]);
+        mfma32_acc(dkacc[db], dsa[qb][h], op[x % RD], db == 0);   // db == 0: first reader of dsa[qb][h]
       else
-        dvacc[db] = mfma32(pa[qb][h], op[x % RD], dvacc[db]);
+        mfma32_acc(dvacc[db], pa[qb][h], op[x % RD], db == 0);    // ... of pa[qb][h]
     }
     // --- the workgroup step and the copies behind it
     if (x == XS) {
@@ -553,9 +573,9 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
     }
     // --- fetch the operand of step x + RD (of the next tile once this one is used up)
     if (x + RD < NX)
-      op[x % RD] = dkdv_operand<D>(qs, x + RD, a_base, t_base0, t_base1);
+      op[x % RD] = dkdv_operand<D>(bs_cur, x + RD);
     else
-      op[x % RD] = dkdv_operand<D>(ah.nqs, x + RD - NX, a_base, t_base0, t_base1);
+      op[x % RD] = dkdv_operand<D>(bs_next, x + RD - NX);
     // --- vector work riding along.  Vector step j = x - NST - stage handles EPS elements of
     //     block j / NST: stage A at x, stage B one step later, stage C two steps later.
     if (x == NST - 1) vec_group(0, 0);
@@ -600,7 +620,7 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   using C = DkdvCfg<D>;
   constexpr int QT = C::QT, NDB = D / 32, NKK = D / 16;
   static_assert(QT == 64, "the tile loop is written for two 32-row blocks per tile");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(256))) char smem[];   // dkdv_operand relies on the alignment
 
   const i32x4 rec = queue_take(a.order_dkdv, a.slots_dkdv, (int*)(smem + C::CNT_OFF) + 8);
   const int unit = rec[0], i_lo = rec[1], i_hi = rec[2];
@@ -742,9 +762,11 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     barrier_nofence();
     int e_cur = __builtin_amdgcn_readfirstlane(list[0]);
 #pragma unroll
-    for (int x = 0; x < C::RD; ++x) op[x] = dkdv_operand<D>(smem + C::STAGE_OFF, x, a_base, t_base0, t_base1);
+    for (int x = 0; x < C::RD; ++x)
+      op[x] = dkdv_operand<D>(dkdv_bases(smem + C::STAGE_OFF, a_base, t_base0, t_base1), x);
     FM_TILE_LOOP(0, n_plain, false)
     FM_TILE_LOOP(n_plain, n_live, true)
+    mfma_acc_drain();  // dkacc / dvacc are read by ordinary code after the loops over heads and chunks
     async_wait<0>();   // the copies made for entries past the end must not outlive the list / the workgroup
     __syncthreads();   // the ring is refilled by the next head, the list rebuilt by the next chunk
     }  // query heads

@@ -55,10 +55,32 @@ __device__ __forceinline__ MinMax8 load_minmax(const int* __restrict__ table, in
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+// The same product accumulated in place in accumulation registers (AGPRs).  For accumulators that
+// live through a whole tile loop and are touched by nothing but their own MFMAs: the compiler picks
+// one register file for all of a kernel's MFMA results, and keeping these in the vector file leaves the
+// loop's vector work half the registers.  The compiler does not look into the asm, so the wait states
+// an MFMA needs are the caller's business:
+//  - a vector instruction that writes an A/B source must be two wait states ahead of the MFMA: pass
+//    fresh = true (a constant once the caller's step loop is unrolled) for the first MFMA that reads
+//    a source just produced by vector instructions (it puts an idle instruction of two cycles in
+//    front); sources loaded from LDS only need the wait the compiler already inserts for the asm's
+//    operands;
+//  - in-place accumulation with one opcode needs none between dependent MFMAs;
+//  - a reader of `acc` other than this function must be kept clear of the last MFMA (mfma_acc_drain).
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b, bool fresh) {
+  const i32x4 ai = __builtin_bit_cast(i32x4, a), bi = __builtin_bit_cast(i32x4, b);
+  if (fresh)
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(ai), "v"(bi));
+  else
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(ai), "v"(bi));
+}
+// After the last mfma32_acc of a loop nest, in the same block of straight-line code (volatile asm
+// statements keep their order): 48 idle cycles, the depth of the matrix pipe for this instruction
+// (8 passes of 4 cycles) plus the margin the ISA asks for before another instruction reads the result.
+// Code that reads the accumulators must sit behind the loop's exit, where the compiler cannot move it
+// ahead of this.
+__device__ __forceinline__ void mfma_acc_drain() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15"); }
 
-// LDS transpose read: within each block of 16 lanes, lane i addresses 4
-// consecutive 16-bit elements of row (i/4), columns 4*(i%4)..+3 of a 4 x 16
-// matrix; it receives column i of that matrix (4 values, one per row).
 __device__ __forceinline__ bf16x4 lds_read_tr16(const char* lds_generic) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FM_LDS bf16x4*)lds_generic);
 }
