@@ -68,8 +68,9 @@ struct DqCfg {
   static constexpr int STAGE = K_BYTES + V_BYTES + BND_BYTES;
   static constexpr int LIST_CAP = 1024;
   static constexpr int CNT_OFF = LIST_CAP * 4;
-  static constexpr int STAGE_OFF = CNT_OFF + 64;
+  static constexpr int STAGE_OFF = CNT_OFF + 256;   // stages start at multiples of 256 bytes (see the operand reads)
   static constexpr int LDS_BYTES = STAGE_OFF + 2 * STAGE;
+  static_assert(STAGE % 256 == 0 && STAGE_OFF % 256 == 0 && K_BYTES % 256 == 0, "XOR after add");
 };
 
 // RAGGED: see the forward kernel -- loops at the padded length, clamped tile copies, guarded stores.
@@ -77,7 +78,7 @@ template <int D, bool RAGGED, bool GEN>
 __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   using C = DqCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(256))) char smem[];   // the operand reads rely on the alignment
 
   const i32x4 rec = queue_take(a.order_dq, a.slots_dq, (int*)(smem + C::CNT_OFF) + 8);
   const int unit = rec[0], j_lo = rec[1], j_hi = rec[2];
@@ -180,13 +181,16 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
       if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
 
       const char* st = smem + C::STAGE_OFF + (t & 1) * C::STAGE;
-      const char* ks = st;
-      const char* vs = st + C::K_BYTES;
       const int* bnd = (const int*)(st + C::K_BYTES + C::V_BYTES);
 
       const int wcls = entry_wave_class(entry, wave);   // Equation 4 on this wave's own rows
       if (wcls != T_FULLY) {
-        const int a_b = opaque(a_base), t_b0 = opaque(t_base0), t_b1 = opaque(t_base1);
+        // Operand addresses: (stage address + lane part) XOR column offset, + constants.  The stage
+        // address is a multiple of 256 bytes, so the sum keeps the lane part's low byte and the XOR
+        // lands where lane part XOR column offset would put it: one instruction per read, and no
+        // per-(pattern, column) register that lives across tiles.
+        const unsigned st_a = lds_address(st);
+        const unsigned a_s = st_a + (unsigned)a_base, t_s0 = st_a + (unsigned)t_base0, t_s1 = st_a + (unsigned)t_base1;
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
           f32x16 sacc, dpacc;
@@ -198,13 +202,12 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
           constexpr int NS = 2 * NKK, RS = 3, NT = 2 * NDB, RT = 3;
           constexpr int EXPS = (16 + NKK - 2) / (NKK - 1);   // exponentials next to each of the last NKK - 1 dP steps
           auto s_operand = [&](int n) __attribute__((always_inline)) {
-            const char* tile = (n >= NKK) ? vs : ks;
-            return *(const bf16x8*)(tile + kb * 32 * C::L::RS + C::L::add_col(a_b, (n % NKK) * 32));
+            return lds_read_row16((a_s ^ (unsigned)((n % NKK) * 32)) + (n >= NKK ? C::K_BYTES : 0) + kb * 32 * C::L::RS);
           };
           auto t_operand = [&](int n) __attribute__((always_inline)) {
-            const char* krow = ks + (kb * 32 + 16 * (n / NDB)) * C::L::RS;
-            return cat4(lds_read_tr16(krow + C::L::add_col(t_b0, (n % NDB) * 64)),
-                        lds_read_tr16(krow + C::L::add_col(t_b1, (n % NDB) * 64)));
+            const unsigned krow = (kb * 32 + 16 * (n / NDB)) * C::L::RS;
+            return cat4(lds_read_tr16_at((t_s0 ^ (unsigned)((n % NDB) * 64)) + krow),
+                        lds_read_tr16_at((t_s1 ^ (unsigned)((n % NDB) * 64)) + krow));
           };
           bf16x8 ring[RS];
 #pragma unroll
@@ -448,11 +451,6 @@ __device__ __forceinline__ DkdvBases dkdv_bases(const char* qs, int a_base, int 
   const unsigned s = lds_address(qs);
   return DkdvBases{s + (unsigned)a_base, s + (unsigned)t_base0, s + (unsigned)t_base1};
 }
-__device__ __forceinline__ bf16x8 lds_read_row16(unsigned addr) { return *(FM_LDS const bf16x8*)(size_t)addr; }
-__device__ __forceinline__ bf16x4 lds_read_tr16_at(unsigned addr) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FM_LDS bf16x4*)(size_t)addr);
-}
-
 // LDS operand of step x of the list entry whose stage addresses are bs (Q tile, dO tile right behind it)
 template <int D>
 __device__ __forceinline__ bf16x8 dkdv_operand(const DkdvBases& bs, int x) {

@@ -85,6 +85,12 @@ __device__ __forceinline__ bf16x4 lds_read_tr16(const char* lds_generic) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FM_LDS bf16x4*)lds_generic);
 }
 
+// The same reads from an LDS byte address held in a register.
+__device__ __forceinline__ bf16x8 lds_read_row16(unsigned addr) { return *(FM_LDS const bf16x8*)(size_t)addr; }
+__device__ __forceinline__ bf16x4 lds_read_tr16_at(unsigned addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((FM_LDS bf16x4*)(size_t)addr);
+}
+
 __device__ __forceinline__ bf16x8 cat4(bf16x4 lo, bf16x4 hi) {
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
