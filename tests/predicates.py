@@ -73,10 +73,15 @@ def random_eviction(i, j, st):
     return j <= i and i < max(int(st["evict_at"][j]), j + 1)
 
 
+def qk_sparse(i, j, st):
+    a, b = st["q_block"]
+    return j <= i and not st["dropped_keys"][j] and not (a <= i < b)
+
+
 PREDICATES = {
     "full": full, "causal": causal, "sliding_window": sliding_window,
     "document": document, "causal_document": causal_document,
     "shared_question": shared_question, "prefix_lm": prefix_lm,
     "prefix_document": prefix_document, "global_sliding_window": global_sliding_window,
-    "causal_blockwise": causal_blockwise, "random_eviction": random_eviction,
+    "causal_blockwise": causal_blockwise, "random_eviction": random_eviction, "qk_sparse": qk_sparse,
 }

@@ -107,7 +107,7 @@ def test_config_zero_query_closed_form_every_head(name):
 
 
 OTHER_FAMILIES = ["document", "prefix_document", "global_sliding_window", "causal_blockwise", "random_eviction",
-                  "random_intervals"]
+                  "qk_sparse", "random_intervals"]
 
 
 @pytest.mark.parametrize("kind", OTHER_FAMILIES)

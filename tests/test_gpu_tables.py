@@ -9,7 +9,7 @@ from oracle import flashmask_oracle as orc
 pytestmark = pytest.mark.gpu
 
 KINDS = ["full", "causal", "sliding_window", "document", "causal_document", "shared_question", "prefix_lm",
-         "prefix_document", "global_sliding_window", "causal_blockwise", "random_eviction", "random_intervals"]
+         "prefix_document", "global_sliding_window", "causal_blockwise", "random_eviction", "qk_sparse", "random_intervals"]
 
 
 def _tables_equal(vecs_np, N, block_r, block_c):

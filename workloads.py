@@ -166,6 +166,24 @@ def random_eviction_mask(N, evict_at):
     return lts, lte, uts, ute
 
 
+def qk_sparse_mask(N, dropped_keys, q_block):
+    """Causal attention in which some keys and one block of queries take no part: key column j is
+    dropped if dropped_keys[j], query rows [a, b) = q_block see nothing.  (A column carries one
+    lower-triangle interval, so the dropped queries must be one contiguous block; the dropped keys may
+    be any set.)"""
+    lts, lte, uts, ute = causal_mask(N)
+    a, b = q_block
+    j = np.arange(N)
+    first = np.maximum(a, j)                   # first dropped row at or below the diagonal
+    has = first < b
+    lts[:] = np.where(has, first, N)
+    lte[:] = np.where(has, b, N)
+    dk = np.asarray(dropped_keys, dtype=bool)
+    lts[dk] = j[dk]                            # a dropped key: every row from the diagonal down
+    lte[dk] = N
+    return lts, lte, uts, ute
+
+
 # --------------------------------------------------------------------------
 # Span samplers
 # --------------------------------------------------------------------------
@@ -382,6 +400,12 @@ def small_workload(mask_kind: str, N: int, seed: int, B: int = 1, H: int = 1, d:
             keep = rng.random(N) < 0.5
             evict = np.where(keep, N, evict)
             st, vec = {"evict_at": evict}, random_eviction_mask(N, evict)
+        elif mask_kind == "qk_sparse":
+            dropped = rng.random(N) < 0.3
+            a0 = int(rng.integers(0, N))
+            b0 = int(rng.integers(a0, N + 1))
+            st = {"dropped_keys": dropped, "q_block": (a0, b0)}
+            vec = qk_sparse_mask(N, dropped, (a0, b0))
         elif mask_kind == "random_intervals":
             # arbitrary int32 pairs, including inverted, overlapping and out-of-range ones
             vec = tuple(rng.integers(-N // 4, N + N // 4 + 1, size=N).astype(np.int32) for _ in range(4))
