@@ -179,22 +179,31 @@ def cpu_baseline(w, orc, workloads, budget_rows):
 
 def sparsity_sweep(torch, fm, orc, workloads, hip, steps, warmup):
     """Wall time of forward+backward against the fraction of tiles that are not skipped, at the
-    shape of config 4 with causal-document masks (equal and random partitions); least-squares line."""
+    shape of config 4 with the three masks of the paper's sparsity experiment (causal document,
+    document, shared question); least-squares lines per mask and over all points."""
     pts = []
     for w in workloads.sweep_workloads():
         r = run_workload(w, steps, warmup, torch, fm, orc, workloads, hip, False)
-        pts.append({"workload": w.name, "docs": len(w.structure[0]), "block_sparsity": round(r["block_sparsity"], 4),
+        pts.append({"workload": w.name, "mask": w.mask_kind, "parts": len(w.structure[0]),
+                    "block_sparsity": round(r["block_sparsity"], 4),
                     "ms": round(r["ms_per_step"], 4), "tflops": round(r["tflops"], 1)})
         torch.cuda.empty_cache()
-    x = np.array([1.0 - p["block_sparsity"] for p in pts])
-    y = np.array([p["ms"] for p in pts])
-    slope, intercept = np.polyfit(x, y, 1)
-    resid = y - (slope * x + intercept)
-    r2 = 1.0 - float(resid @ resid) / float(((y - y.mean()) @ (y - y.mean())))
+
+    def fit(sel):
+        x = np.array([1.0 - p["block_sparsity"] for p in sel])
+        y = np.array([p["ms"] for p in sel])
+        slope, intercept = np.polyfit(x, y, 1)
+        resid = y - (slope * x + intercept)
+        r2 = 1.0 - float(resid @ resid) / float(((y - y.mean()) @ (y - y.mean())))
+        return {"points": len(sel), "slope_ms": round(float(slope), 4), "intercept_ms": round(float(intercept), 4),
+                "r2": round(r2, 5)}
+
+    fits = {"all": fit(pts)}
+    for kind in sorted({p["mask"] for p in pts}):
+        fits[kind] = fit([p for p in pts if p["mask"] == kind])
     return {"metric": "fwd+bwd ms vs fraction of 128x128 tiles not skipped (1 - block sparsity)",
-            "shape": "B=1, H=16, N=32768, d=128, causal-document masks", "steps": steps, "warmup": warmup,
-            "fit": {"slope_ms": round(float(slope), 4), "intercept_ms": round(float(intercept), 4), "r2": round(r2, 5)},
-            "points": pts}
+            "shape": "B=1, H=16, N=32768, d=128; causal-document, document and shared-question masks",
+            "steps": steps, "warmup": warmup, "fit": fits["all"], "fits": fits, "points": pts}
 
 
 def paper_table(torch, fm, orc, workloads, hip, steps, warmup):

@@ -313,7 +313,9 @@ CONFIG_NAMES = ("1", "2", "3", "4a", "4b", "5")
 def sweep_workloads(n_random: int = 20):
     """Workloads of the block-sparsity sweep: the shape of config 4 (B=1, H=16, N=32768, d=128)
     with causal-document masks of 1, 2, 4, ..., 128 equal documents and `n_random` seeded random
-    partitions (2..64 documents, uniform composition with floor 128)."""
+    partitions (2..64 documents, uniform composition with floor 128), then bidirectional document
+    masks (the same equal partitions and n_random / 2 random ones) and n_random / 2 shared-question
+    masks of growing sample size."""
     out = []
     N = 32768
     for k, n_docs in enumerate((1, 2, 4, 8, 16, 32, 64, 128)):
@@ -329,6 +331,28 @@ def sweep_workloads(n_random: int = 20):
         spans = spans_from_lengths(sample_partition(rng, N, n_docs, 128))
         w.structure = [spans]
         w.vectors = [causal_document_mask(N, spans)]
+        out.append(w)
+    # the other two masks of the paper's sparsity experiment: bidirectional documents and shared questions
+    for k, n_docs in enumerate((1, 2, 4, 8, 16, 32, 64, 128)):
+        w = Workload(f"sweep-doc-eq{n_docs}", 1, 16, N, 128, BASE_SEED + 700 + k, "document")
+        spans = spans_from_lengths([N // n_docs] * n_docs)
+        w.structure = [spans]
+        w.vectors = [document_mask(N, spans)]
+        out.append(w)
+    for k in range(n_random // 2):
+        w = Workload(f"sweep-doc-rand{k}", 1, 16, N, 128, BASE_SEED + 720 + k, "document")
+        rng = _mask_rng(w.seed)
+        spans = spans_from_lengths(sample_partition(rng, N, int(rng.integers(2, 65)), 128))
+        w.structure = [spans]
+        w.vectors = [document_mask(N, spans)]
+        out.append(w)
+    for k in range(n_random // 2):
+        w = Workload(f"sweep-sq{k}", 1, 16, N, 128, BASE_SEED + 740 + k, "shared_question")
+        rng = _mask_rng(w.seed)
+        f = 2 ** (k % 5)                       # sample sizes from the config-3 recipe up to 16 times that
+        samples = sample_shared_question(rng, N, (512 * f, 2048 * f), (256 * f, 1024 * f), (2, 4))
+        w.structure = [samples]
+        w.vectors = [shared_question_mask(N, samples)]
         out.append(w)
     return out
 
