@@ -1,0 +1,77 @@
+"""Host-side check of the wait states around the dK/dV loop's inline-assembly MFMAs.
+
+The two accumulating products of the dK/dV kernel are issued from inline assembly so that their
+accumulators live in AGPRs; the compiler does not look into the asm, so the wait states it would
+insert for an ordinary MFMA are the source's responsibility (see mfma32_acc in fm_common.h).  This
+test compiles the backward source to gfx950 assembly (no GPU needed, ~15 s) and checks, in every
+instantiation of the kernel, what the source relies on:
+  * no vector instruction writes an A/B source of such an MFMA within the two instructions before
+    it, unless the MFMA carries its own idle instruction (`s_nop 1`);
+  * the accumulator registers are written only by their zero-initialisation and by these MFMAs, and
+    read only once each (the epilogue), and the kernel holds the drain (`s_nop 15` x 3).
+"""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _assembly(tmp_path):
+    import importlib
+    build = importlib.import_module("paper_2410_01359_amd.build")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    out = os.path.join(tmp_path, "fm_bwd.s")
+    flags = [f for f in build.FLAGS if f != "-shared"]
+    cmd = [hipcc, *flags, "--cuda-device-only", "-S", os.path.join(build.CSRC, "fm_bwd.hip"), "-o", out]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE, timeout=600)
+    return open(out).read()
+
+
+def _regs(text, prefix):
+    """Register numbers named in an operand string, for v (prefix 'v') or a (prefix 'a') registers."""
+    regs = set()
+    for lo, hi in re.findall(r"\b%s\[(\d+):(\d+)\]" % prefix, text):
+        regs.update(range(int(lo), int(hi) + 1))
+    regs.update(int(x) for x in re.findall(r"\b%s(\d+)\b" % prefix, text))
+    return regs
+
+
+def test_dkdv_inline_asm_mfma_wait_states(tmp_path):
+    asm = _assembly(str(tmp_path))
+    kernels = list(re.finditer(r"^(_ZN2fm11dkdv_kernel\w+):.*?^\.Lfunc_end\d+:", asm, re.S | re.M))
+    assert len(kernels) == 8, "two head dims x ragged x general"
+    for m in kernels:
+        name = m.group(1)
+        lines = [l.strip() for l in m.group(0).split("\n")]
+        real = [l for l in lines if l and not l.startswith(";") and not l.startswith(".") and not l.endswith(":")]
+        is_acc_mfma = lambda l: l.startswith("v_mfma_f32_32x32x16_bf16 a")
+        accs = set()
+        n_mfma = 0
+        for k, l in enumerate(real):
+            if not is_acc_mfma(l):
+                continue
+            n_mfma += 1
+            dst, rest = l.split(",", 1)
+            accs |= _regs(dst, "a")
+            srcs = _regs(rest, "v")
+            if real[k - 1] == "s_nop 1":
+                continue
+            for prev in real[max(0, k - 2):k]:
+                w = re.match(r"v_(?!mfma)\w+ (v\d+|v\[\d+:\d+\])", prev)
+                assert not (w and _regs(w.group(1), "v") & srcs), f"{name}: '{prev}' right before '{l}'"
+        d = 128 if "ILi128E" in name else 64
+        assert n_mfma == 2 * (d // 32) * 8, f"{name}: {n_mfma} accumulating MFMAs"   # (dK + dV) x d/32 blocks x 8 steps
+        assert len(accs) == 4 * d // 32 * 16 // 2, f"{name}: {len(accs)} accumulator registers"
+        reads = [l for l in real if l.startswith("v_accvgpr_read") and _regs(l.split(",", 1)[1], "a") & accs]
+        assert len(reads) == len(accs), f"{name}: accumulators read {len(reads)} times for {len(accs)} registers"
+        for l in real:
+            if is_acc_mfma(l) or l.startswith("v_accvgpr"):
+                continue
+            assert not (_regs(l, "a") & accs), f"{name}: '{l}' touches an accumulator register"
+        assert sum(1 for l in real if l == "s_nop 15") >= 3, f"{name}: drain missing"
