@@ -92,6 +92,31 @@ def test_paper_printed_sparsity_and_tflops(mask, n, bh, fw, bw, rho):
     assert abs(got_bw / 1e12 - bw) <= 0.0151, (got_bw / 1e12, bw)
 
 
+@pytest.mark.parametrize("mask,n,bh,fw,bw,rho", [r for r in _golden_rows() if r[0] == "full"])
+def test_elementwise_flop_model_reproduces_printed_full_mask_rows(mask, n, bh, fw, bw, rho):
+    """flops_elem (the headline's numerator) on the Full mask, where every element is unmasked, must
+    give the FW / BW TFLOPs the paper prints for its Full rows (d = 128 kernel tables): 17.59 / 43.98,
+    70.37 / 175.92, 281.48 / 703.69 (printed to two decimals; 281.47 computed)."""
+    vec = workloads.full_mask(n)
+    unmasked = orc.count_unmasked_elements(*vec)
+    assert unmasked == n * n
+    got_fw, got_bw = orc.flops_elem(unmasked, bh, 128)
+    assert abs(got_fw / 1e12 - fw) <= 0.0101, (got_fw / 1e12, fw)
+    assert abs(got_bw / 1e12 - bw) <= 0.0151, (got_bw / 1e12, bw)
+    assert got_bw == 2.5 * got_fw
+
+
+def test_elementwise_flops_equal_tile_flops_where_no_tile_is_partial():
+    """A mask whose boundaries all fall on multiples of 128 has no partially masked tile, so the
+    element count and the tile count of the FLOP model agree exactly."""
+    n = 2048
+    vec = workloads.document_mask(n, workloads.spans_from_lengths([512, 256, 1024, 256]))
+    cls = orc.classify_tiles(orc.minmax_tables(*vec, 128), n, 128, 128)
+    assert not ((cls & 3) == orc.PARTIAL).any()
+    assert orc.flops_elem(orc.count_unmasked_elements(*vec), 3, 128) == orc.flops_tile(cls, 3, 128)
+    assert orc.count_unmasked_elements(*vec) == 512 ** 2 + 2 * 256 ** 2 + 1024 ** 2
+
+
 def test_elementwise_flops_never_exceed_tile_flops():
     for name in ("4a", "4b"):
         w = workloads.config(name)
