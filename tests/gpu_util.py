@@ -6,9 +6,16 @@ import torch
 import workloads
 from oracle import flashmask_oracle as orc
 
-# Parity bars (spec tolerances): out and lse max-abs 2e-2 and, where the
-# reference magnitude is >= 1, relative 1e-2; gradients max-abs 5e-2.
+# Parity bars (spec tolerances): out and lse max-abs 2e-2 and relative 1e-2; gradients
+# max-abs 5e-2.  The relative bar is applied in two forms.  Where the reference magnitude is >= 1 it
+# is the plain elementwise bound.  Everywhere, it is applied with a floor of two bf16 rounding steps
+# (2 x 2^-8: P is rounded to bf16 as a matrix-core operand, out is stored in bf16) of the scale the
+# element lives at: for `out`, the largest magnitude in the element's row (a row of out is one convex
+# combination of V rows, so its entries share that scale); for lse, which is O(1) by construction,
+# 2^-7 itself.  At the benchmark sizes out is an average over many keys (|out| ~ 0.05), so without the
+# floored form only the absolute bar would ever act there.
 ABS_FWD, REL_FWD, ABS_BWD = 2e-2, 1e-2, 5e-2
+REL_FLOOR = 2.0 ** -7
 
 
 def to_device(w: workloads.Workload, names=("q", "k", "v", "dout")):
@@ -35,6 +42,11 @@ def check_fwd(got_out, got_lse, ref_out, ref_lse, what=""):
         if big.any():
             rel = (err[big] / np.abs(r[big])).max()
             assert rel <= REL_FWD, f"{what}: {name} max-rel {rel:.4g} > {REL_FWD}"
+        if err.size:
+            scale_of = np.abs(r).max(axis=-1, keepdims=True) if name == "out" else 1.0
+            excess = err - (REL_FWD * np.abs(r) + REL_FLOOR * scale_of)
+            assert excess.max() <= 0.0, (f"{what}: {name} error exceeds {REL_FWD} * |ref| + 2^-7 * row scale by "
+                                         f"{excess.max():.4g}")
 
 
 def check_bwd(got, ref, name, what=""):

@@ -1,0 +1,157 @@
+"""GPU: EVERY element at the full benchmark sizes, in the launch configuration bench.py times.
+
+Three kinds of evidence, none of them sampled:
+  * configs 2, 3, 4a, 4b: whole heads against the dense fp64 oracle (every element of out, lse, dq,
+    dk, dv); config 5: one whole head, taken in groups of documents (the oracle itself shows that the
+    rows of a group send nothing to the key columns outside it);
+  * configs 2, 4a, 4b, 5, every head: the closed forms of uniform attention (Q = 0, then K = 0 with
+    random Q), built from the task structure in O(N d^2) without any N x N work (closed_forms.py);
+  * all five multi-tile configs: head 0's tensors copied into every head give bit-identical results in
+    every head (and equal to head 0 of the ordinary run), so what the oracle shows for one head holds
+    for the unit-to-head mapping of all of them.
+"""
+import functools
+
+import numpy as np
+import pytest
+import torch
+
+import closed_forms as cf
+import workloads
+from gpu_util import ABS_BWD, ABS_FWD, bf16_to_np, check_bwd, check_fwd, f64, to_device
+from oracle import flashmask_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+@functools.lru_cache(maxsize=1)
+def gpu_results(name):
+    """Forward + backward of a whole configuration on its seeded inputs (kept for the tests of one
+    configuration, which run back to back)."""
+    import paper_2410_01359_amd as fm
+    w = workloads.config(name)
+    bits, dev, vecs = to_device(w)
+    out, lse = fm.flashmask_fwd(dev["q"], dev["k"], dev["v"], *vecs, w.scale)
+    dq, dk, dv = fm.flashmask_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], *vecs, w.scale)
+    torch.cuda.synchronize()
+    del dev
+    return w, bits, {"out": out, "lse": lse, "dq": dq, "dk": dk, "dv": dv}
+
+
+def whole_head_cases():
+    cases = []
+    for name, heads in (("2", (0, 5, 11, 16, 21, 26, 31)), ("3", (0, 5, 11, 16, 21, 26, 31)),
+                        ("4a", (0, 8, 15)), ("4b", (0, 8, 15))):
+        for b in range(2 if name == "2" else 1):
+            for h in heads:
+                cases.append((name, b, h))
+    return cases
+
+
+@pytest.mark.parametrize("name,b,h", whole_head_cases())
+def test_whole_head_every_element_against_oracle(name, b, h):
+    w, bits, got = gpu_results(name)
+    args = [f64(bits[n][b, h]) for n in ("q", "k", "v", "dout")]
+    rdq, rdk, rdv, ro, rl = orc.backward(*args, *w.vectors[b], w.scale)
+    what = f"config {name} b={b} h={h}"
+    check_fwd(bf16_to_np(got["out"][b, h]), got["lse"][b, h].cpu().numpy(), ro, rl, what)
+    check_bwd(bf16_to_np(got["dq"][b, h]), rdq, "dq", what)
+    check_bwd(bf16_to_np(got["dk"][b, h]), rdk, "dk", what)
+    check_bwd(bf16_to_np(got["dv"][b, h]), rdv, "dv", what)
+
+
+def config5_groups(n_groups=5):
+    """Consecutive documents of config 5 in groups of about N / n_groups rows: [(row0, row1), ...]."""
+    spans = workloads.config("5").structure[0]
+    groups, start, target = [], 0, workloads.config("5").N // n_groups
+    for s, e in spans:
+        if e - start >= target or e == spans[-1][1]:
+            groups.append((start, e))
+            start = e
+    return groups
+
+
+@pytest.mark.parametrize("rows", config5_groups())
+def test_config5_whole_head_by_document_groups(rows):
+    """Head 3 of config 5 (N = 131072), every element.  A group is a run of whole documents: its rows see
+    no key outside it, which the oracle's own dk / dv contributions confirm (exactly zero outside), so
+    the group's rows give the complete dk, dv of the group's columns."""
+    w, bits, got = gpu_results("5")
+    h, (r0, r1) = 3, rows
+    args = [f64(bits[n][0, h]) for n in ("q", "k", "v", "dout")]
+    vec = w.vectors[0]
+    dk = np.zeros((r1 - r0, w.d))
+    dv = np.zeros((r1 - r0, w.d))
+    what = f"config 5 h={h} rows {r0}:{r1}"
+    for c0 in range(r0, r1, 2048):
+        r = np.arange(c0, min(c0 + 2048, r1))
+        dq_r, dk_part, dv_part, out_r, lse_r = orc.backward_row_block(*args, *vec, w.scale, r)
+        assert not dk_part[:r0].any() and not dk_part[r1:].any() and not dv_part[:r0].any() and not dv_part[r1:].any()
+        dk += dk_part[r0:r1]
+        dv += dv_part[r0:r1]
+        check_fwd(bf16_to_np(got["out"][0, h][r]), got["lse"][0, h][r].cpu().numpy(), out_r, lse_r, what)
+        check_bwd(bf16_to_np(got["dq"][0, h][r]), dq_r, "dq", what)
+    check_bwd(bf16_to_np(got["dk"][0, h][r0:r1]), dk, "dk", what)
+    check_bwd(bf16_to_np(got["dv"][0, h][r0:r1]), dv, "dv", what)
+
+
+@pytest.mark.parametrize("zero", ["q", "k"])
+@pytest.mark.parametrize("name", ["2", "4a", "4b", "5"])
+def test_uniform_attention_closed_forms_every_head_every_element(name, zero):
+    """Q = 0 (then K = 0 with the seeded Q): every score is 0, P is uniform over the visible keys, and
+    all five outputs have closed forms as prefix sums over the document / window / prefix structure.
+    Q = 0 exercises dq (and dk == 0 exactly), K = 0 exercises dk (and dq == 0 exactly); dv, out, lse in both."""
+    import paper_2410_01359_amd as fm
+    gpu_results.cache_clear()
+    w = workloads.config(name)
+    bits, dev, vecs = to_device(w)
+    dev[zero] = torch.zeros_like(dev[zero])
+    out, lse = fm.flashmask_fwd(dev["q"], dev["k"], dev["v"], *vecs, w.scale)
+    dq, dk, dv = fm.flashmask_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], *vecs, w.scale)
+    torch.cuda.synchronize()
+    exact_zero = dk if zero == "q" else dq
+    assert not exact_zero.float().abs().max().item() > 0.0, f"d{'k' if zero == 'q' else 'q'} must be exactly zero"
+    for b in range(w.B):
+        a, e, r, bb = cf.ranges_of(w, b)
+        for h in range(w.H):
+            q, k, v, do = (f64(bits[n][b, h]) for n in ("q", "k", "v", "dout"))
+            if zero == "q":
+                q = np.zeros_like(q)
+            else:
+                k = np.zeros_like(k)
+            what = f"config {name} {zero}=0 b={b} h={h}"
+            ref_lse, ref_out = cf.forward_uniform(v, a, e)
+            check_fwd(bf16_to_np(out[b, h]), lse[b, h].cpu().numpy(), ref_out, ref_lse, what)
+            # the kernels form D from their own bf16 out (Algorithm 2 takes O as an input)
+            rdq, rdk, rdv = cf.backward_uniform(q, k, v, do, w.scale, a, e, r, bb,
+                                                out=bf16_to_np(out[b, h]).astype(np.float64))
+            check_bwd(bf16_to_np(dv[b, h]), rdv, "dv", what)
+            check_bwd(bf16_to_np(dq[b, h]), rdq, "dq", what)
+            check_bwd(bf16_to_np(dk[b, h]), rdk, "dk", what)
+
+
+@pytest.mark.parametrize("name", ["2", "3", "4a", "4b", "5"])
+def test_replicated_heads_are_bit_identical(name):
+    """Head 0 of batch row 0 copied into every head, and batch row 0's mask into every batch row: every
+    (batch row, head) must then produce the same bits (each unit's arithmetic is fixed; only the queue,
+    the XCD and the addresses differ), and the same bits as head 0 of the ordinary run, which the tests
+    above and the sampled ones compare with the oracle."""
+    import paper_2410_01359_amd as fm
+    w, bits, got = gpu_results(name)
+    first = {k: t[0, 0].clone() for k, t in got.items()}
+    gpu_results.cache_clear()
+    del got
+    dev = {}
+    for n in ("q", "k", "v", "dout"):
+        one = torch.from_numpy(bits[n][0, 0].view(np.int16)).view(torch.bfloat16).cuda()
+        dev[n] = one[None, None].expand(w.B, w.H, w.N, w.d).contiguous()
+    vecs = tuple(torch.from_numpy(np.asarray(x, dtype=np.int32)[None].repeat(w.B, 0)).cuda() for x in w.vectors[0])
+    out, lse = fm.flashmask_fwd(dev["q"], dev["k"], dev["v"], *vecs, w.scale)
+    dq, dk, dv = fm.flashmask_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], *vecs, w.scale)
+    torch.cuda.synchronize()
+    for key, t in (("out", out), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
+        ref = first[key]
+        same = (t.view(w.B * w.H, -1).view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32) ==
+                ref.reshape(1, -1).view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)).all(dim=1)
+        bad = (~same).nonzero().flatten().tolist()
+        assert not bad, f"config {name}: {key} differs from head 0 in (b*H + h) = {bad[:8]}"
