@@ -50,7 +50,8 @@ enum {
   FM_ERR_ALIGN = -3,     /* a tensor pointer is not 16-byte aligned */
   FM_ERR_WORKSPACE = -4, /* workspace is NULL or smaller than flashmask_workspace_bytes() */
   FM_ERR_HIP = -5,       /* a kernel launch failed; see flashmask_last_hip_error() */
-  FM_ERR_ARG = -6        /* unknown pass id, scale <= 0 or not finite */
+  FM_ERR_ARG = -6,       /* unknown pass id, scale <= 0 or not finite */
+  FM_ERR_STATIC_LIMIT = -7 /* flashmask_fwd_noalloc: the problem does not fit the library's static scratch */
 };
 
 /* Pass ids for flashmask_workspace_bytes / flashmask_tile_shape. */
@@ -110,6 +111,29 @@ int flashmask_bwd(const void* q, const void* k, const void* v,
                   float scale, void* dq, void* dk, void* dv,
                   int B, int H, int N, int d,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * flashmask_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic,
+ * kernels and results as flashmask_fwd, but the scratch (min/max tables, work counts, unit queues,
+ * padded bound vectors) lives in a static device array inside the library instead of a caller's
+ * workspace.  The call allocates and frees nothing.
+ *   - Limit: flashmask_workspace_bytes(FM_PASS_FWD, B, H, N, d) must not exceed
+ *     FLASHMASK_NOALLOC_SCRATCH_BYTES (4 MiB: about 250 000 row blocks of 128 queries over all batch
+ *     rows and heads, e.g. B*H = 512 at N = 65536); larger problems return FM_ERR_STATIC_LIMIT and
+ *     launch nothing.  Each GPU the library runs on holds its own copy of the array until the process
+ *     ends.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress) and, like
+ *     flashmask_fwd, raises the tile loop's dynamic-LDS limit: issue one call outside a capture first.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU
+ *     (different streams or threads) race.  Calls on one stream, or otherwise ordered, are fine; the
+ *     array's contents carry nothing from one call to the next.
+ */
+#define FLASHMASK_NOALLOC_SCRATCH_BYTES (4u << 20)
+int flashmask_fwd_noalloc(const void* q, const void* k, const void* v,
+                          const int32_t* lts, const int32_t* lte, const int32_t* uts, const int32_t* ute,
+                          float scale, void* out, float* lse,
+                          int B, int H, int N, int d, void* hip_stream);
 
 /*
  * Layout of a bf16 tensor indexed [batch][head][row][d] for the *_ex entry points: distances, in

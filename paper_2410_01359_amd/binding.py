@@ -43,6 +43,8 @@ def load_library() -> ctypes.CDLL:
     i, f, sz = ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.flashmask_fwd.restype = i
     lib.flashmask_fwd.argtypes = [vp, vp, vp, ip, ip, ip, ip, f, vp, fp, i, i, i, i, vp, sz, vp]
+    lib.flashmask_fwd_noalloc.restype = i
+    lib.flashmask_fwd_noalloc.argtypes = [vp, vp, vp, ip, ip, ip, ip, f, vp, fp, i, i, i, i, vp]
     lib.flashmask_bwd.restype = i
     lib.flashmask_bwd.argtypes = [vp, vp, vp, vp, fp, vp, ip, ip, ip, ip, f, vp, vp, vp, i, i, i, i, vp, sz, vp]
     sp = ctypes.POINTER(Strides)
@@ -146,6 +148,25 @@ def flashmask_fwd(q, k, v, lts, lte, uts, ute, scale: float, workspace: torch.Te
     _check(load_library().flashmask_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), lts.data_ptr(), lte.data_ptr(),
                                         uts.data_ptr(), ute.data_ptr(), float(scale), out.data_ptr(), lse.data_ptr(),
                                         B, H, N, d, ws.data_ptr(), ws.numel(), _stream()), "flashmask_fwd")
+    return out, lse
+
+
+def flashmask_fwd_noalloc(q, k, v, lts, lte, uts, ute, scale: float, out: torch.Tensor, lse: torch.Tensor):
+    """flashmask_fwd into caller-provided out / lse, with the library's static scratch: this call
+    itself allocates nothing (not even through torch)."""
+    for t, n in zip((q, k, v, out), ("q", "k", "v", "out")):
+        _dev(t, torch.bfloat16, n)
+    _dev(lse, torch.float32, "lse")
+    for t, n in zip((lts, lte, uts, ute), ("lts", "lte", "uts", "ute")):
+        _dev(t, torch.int32, n)
+    B, H, N, d = q.shape
+    if any(x.shape != q.shape for x in (k, v, out)) or tuple(lse.shape) != (B, H, N) or \
+            any(tuple(x.shape) != (B, N) for x in (lts, lte, uts, ute)):
+        raise FlashMaskError("shape mismatch: q,k,v,out [B,H,N,d]; lse [B,H,N]; lts,lte,uts,ute [B,N]")
+    _check(load_library().flashmask_fwd_noalloc(q.data_ptr(), k.data_ptr(), v.data_ptr(), lts.data_ptr(),
+                                                lte.data_ptr(), uts.data_ptr(), ute.data_ptr(), float(scale),
+                                                out.data_ptr(), lse.data_ptr(), B, H, N, d, _stream()),
+           "flashmask_fwd_noalloc")
     return out, lse
 
 

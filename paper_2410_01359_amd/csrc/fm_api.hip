@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation, workspace carving, launches.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 
@@ -21,6 +22,27 @@ hipEvent_t* g_prof_events = nullptr;
 int g_prof_count = 0;
 inline void mark(int idx, hipStream_t stream) {
   if (g_prof_events && idx < g_prof_count && g_prof_events[idx]) (void)hipEventRecord(g_prof_events[idx], stream);
+}
+
+// Scratch of flashmask_fwd_noalloc: one copy per device, part of the library's code object.  In host
+// code the name below only stands for the symbol; the memory's address on the current device comes from
+// hipGetSymbolAddress (static_scratch) and is what kernels, copies and clears must be given.
+static __device__ __align__(256) unsigned char scratch[FLASHMASK_NOALLOC_SCRATCH_BYTES];
+std::atomic<void*> g_scratch_ptr[FM_MAX_DEVICES];
+
+// Address of `scratch` on the current device, looked up once per device.
+hipError_t static_scratch(void** ptr) {
+  int dev = 0;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  if (dev < 0 || dev >= FM_MAX_DEVICES) return hipErrorInvalidDevice;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread looks up the same address
+  }
+  *ptr = p;
+  return hipSuccess;
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -85,6 +107,9 @@ const char* flashmask_strerror(int code) {
     case FM_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
     case FM_ERR_HIP: return "HIP launch failed (see flashmask_last_hip_error)";
     case FM_ERR_ARG: return "bad scalar argument (unknown pass id, or scale not a positive finite number)";
+    case FM_ERR_STATIC_LIMIT:
+      return "flashmask_fwd_noalloc: the problem needs more scratch than the library's static buffer holds "
+             "(flashmask_workspace_bytes(FM_PASS_FWD, ...) > FLASHMASK_NOALLOC_SCRATCH_BYTES)";
     default: return "unknown flashmask error code";
   }
 }
@@ -235,6 +260,20 @@ int flashmask_fwd(const void* q, const void* k, const void* v, const int32_t* lt
                   int d, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return fwd_impl(q, k, v, lts, lte, uts, ute, scale, out, lse, B, H, H, N, d, nullptr, workspace, workspace_bytes,
                   hip_stream);
+}
+
+int flashmask_fwd_noalloc(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
+                          const int32_t* uts, const int32_t* ute, float scale, void* out, float* lse, int B, int H,
+                          int N, int d, void* hip_stream) {
+  if (int rc = check_shape(B, H, N, d)) return rc;
+  const size_t need = flashmask_workspace_bytes(FM_PASS_FWD, B, H, N, d);
+  if (need > (size_t)FLASHMASK_NOALLOC_SCRATCH_BYTES) return FM_ERR_STATIC_LIMIT;
+  void* ws = nullptr;
+  if (hipError_t e = static_scratch(&ws); e != hipSuccess) return hip_fail(e);
+  // every word of the scratch that a call reads it writes first (tables, work counts, queue records,
+  // queue counters: the queue-building kernel clears them), so what the previous call left is harmless
+  return fwd_impl(q, k, v, lts, lte, uts, ute, scale, out, lse, B, H, H, N, d, nullptr, ws,
+                  FLASHMASK_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 int flashmask_fwd_ex(const void* q, const void* k, const void* v, const int32_t* lts, const int32_t* lte,
