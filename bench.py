@@ -126,6 +126,89 @@ def run_workload(name, steps, warmup, torch, fm, orc, workloads, hip, with_event
     return res
 
 
+def kernels_digest():
+    """Digest of the HIP sources: recorded with the counter-derived traffic figures, which are only
+    reported while the kernels they were measured on are the ones being timed."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2410_01359_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_traffic():
+    """profiles/hbm_traffic.json: {"kernels_digest": ..., "entries": {"<workload>:<kernel>": bytes per launch}}
+    written from rocprofv3 FETCH_SIZE / WRITE_SIZE runs.  Entries measured on other kernels are not used."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except Exception:
+        return {}, "no profiles/hbm_traffic.json"
+    if rec.get("kernels_digest") != kernels_digest():
+        return {}, "profiles/hbm_traffic.json was measured on other kernel sources; traffic not reported"
+    return rec.get("entries", {}), None
+
+
+def roofline_of(res, traffic_entries, onbox):
+    """The tile loop with the largest event-timed duration of one workload against the bf16 MFMA peak."""
+    st = res["stage_ms"]
+    dominant = max(("fwd_tiles", "bwd_dkdv", "bwd_dq"), key=lambda k: st[k])
+    achieved = res["kernel_flop"][dominant] / st[dominant] / 1e9
+    roof = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+            "traffic": traffic_entries.get(f"{res['workload']}:{dominant}"),
+            "kernel_ms": round(st[dominant], 4),
+            "all_loops_tflops": {k: round(res["kernel_flop"][k] / st[k] / 1e9, 1) for k in ("fwd_tiles", "bwd_dkdv", "bwd_dq")}}
+    if onbox:
+        roof["onbox_peak"] = onbox["tflops"]
+        roof["frac_of_onbox_peak"] = round(achieved / onbox["tflops"], 4)
+    return roof
+
+
+def backward_rates(res):
+    """The backward's rate on the five matrix products Algorithm 2 has (10 d FLOP per unmasked element:
+    what the metric counts) beside its rate on the seven it executes (the row-parallel dQ pass forms S and
+    dP a second time: 14 d)."""
+    counted = 2.5 * res["kernel_flop"]["fwd_tiles"]
+    executed = res["kernel_flop"]["bwd_dkdv"] + res["kernel_flop"]["bwd_dq"]
+    return {"alg2_products_tflops": round(counted / res["bwd_ms"] / 1e9, 1),
+            "executed_products_tflops": round(executed / res["bwd_ms"] / 1e9, 1),
+            "alg2_frac_of_peak": round(counted / res["bwd_ms"] / 1e9 / PEAK_BF16_TFLOPS, 4)}
+
+
+def mfma_ceiling(torch, fm, hip, iters=4000, reps=5):
+    """On-box matrix-core ceiling: a kernel of nothing but the bf16 32x32x16 MFMA on random operands, the
+    whole chip filled as the tile loops fill it (2 workgroups of 4 waves per CU), timed with events on the
+    launch stream.  `implied_clock_ghz` = rate / (256 CUs x 4096 FLOP per clock): the clock the chip held if
+    every SIMD issued back to back."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    operands = torch.randn(8192, device="cuda", generator=g).bfloat16()
+    wgs = 256 * 2 * 4                      # four rounds of full occupancy
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    fm.flashmask_mfma_ceiling(operands, sink, wgs, iters // 10)
+    torch.cuda.synchronize()
+    best = None
+    ev = make_events(hip, 2)
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    for _ in range(reps):
+        hip.hipEventRecord(ev[0], ctypes.c_void_p(stream))
+        flop = fm.flashmask_mfma_ceiling(operands, sink, wgs, iters)
+        hip.hipEventRecord(ev[1], ctypes.c_void_p(stream))
+        hip.hipEventSynchronize(ev[1])
+        ms = elapsed(hip, ev[0], ev[1])
+        best = ms if best is None else min(best, ms)
+    for e in ev:
+        hip.hipEventDestroy(e)
+    tflops = flop / best / 1e9
+    return {"tflops": round(tflops, 1), "ms": round(best, 4), "implied_clock_ghz": round(tflops * 1e12 / (256 * 4096) / 1e9, 3),
+            "kernel": "v_mfma_f32_32x32x16_bf16 only, random operands, 2048 workgroups x 4 waves, 4 chains per wave"}
+
+
 def forward_only_grouped(torch, fm, orc, workloads, steps):
     """Forward pass alone at the head configuration of the paper's inference appendix (32 query
     heads on 8 K/V heads, d = 128, batch 1) under a causal-document mask of 16 equal documents at
@@ -243,6 +326,8 @@ def main():
     ap.add_argument("--paper-table", action="store_true",
                     help="instead of the benchmark line, time the deterministic rows of the paper's d=128 "
                          "kernel-speed tables (128K tokens, 32 heads, N = 8K / 32K / 128K)")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="only measure the on-box matrix-core ceiling (an MFMA-only kernel) and print it")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (read once, written once): a kernel of known "
                          "HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -263,6 +348,10 @@ def main():
     fm.load_library()
     hip = hip_runtime()
 
+    if args.mfma_ceiling:
+        print(json.dumps(mfma_ceiling(torch, fm, hip)), flush=True)
+        return
+
     if args.sweep:
         print(json.dumps(sparsity_sweep(torch, fm, orc, workloads, hip, max(3, args.steps // 4), 2)), flush=True)
         return
@@ -271,6 +360,8 @@ def main():
         print(json.dumps(paper_table(torch, fm, orc, workloads, hip, max(2, args.steps // 5), 1)), flush=True)
         return
 
+    onbox = mfma_ceiling(torch, fm, hip)
+    traffic_entries, traffic_note = load_traffic()
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, fm, orc, workloads, hip, True)
     w = main_res.pop("workload_obj")
     others = []
@@ -279,9 +370,13 @@ def main():
         r.pop("workload_obj")
         r["pct_of_bf16_mfma_peak"] = 100.0 * r["tflops"] / PEAK_BF16_TFLOPS
         r["tile_tflops"] = r["tile_tflop"] * 1e3 / r["ms_per_step"]      # the paper's accounting: 128x128 tiles not skipped
-        others.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
-                       if k in ("workload", "ms_per_step", "tflops", "pct_of_bf16_mfma_peak", "tile_tflops",
-                                "block_sparsity", "unmasked_tflop", "tile_tflop", "fwd_ms", "bwd_ms")})
+        entry = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                 if k in ("workload", "ms_per_step", "tflops", "pct_of_bf16_mfma_peak", "tile_tflops",
+                          "block_sparsity", "unmasked_tflop", "tile_tflop", "fwd_ms", "bwd_ms")}
+        entry["stage_ms"] = {k: round(v, 4) for k, v in r["stage_ms"].items()}
+        entry["roofline"] = roofline_of(r, traffic_entries, onbox)
+        entry["backward"] = backward_rates(r)
+        others.append(entry)
         torch.cuda.empty_cache()
 
     if args.copy_calibration_mib > 0:
@@ -294,15 +389,9 @@ def main():
         del src, dst
 
     st = main_res["stage_ms"]
-    dominant = max(("fwd_tiles", "bwd_dkdv", "bwd_dq"), key=lambda k: st[k])
-    achieved = main_res["kernel_flop"][dominant] / st[dominant] / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(f"{args.workload}:{dominant}")
-        except Exception:
-            traffic = None
+    roof = roofline_of(main_res, traffic_entries, onbox)
+    if traffic_note:
+        roof["traffic_note"] = traffic_note
     line = {
         "metric": "fwd+bwd TFLOPs/s (unmasked FLOPs) on 1 MI355X",
         "value": round(main_res["tflops"], 2),
@@ -319,8 +408,9 @@ def main():
                    "tile_tflop_per_step": round(main_res["tile_tflop"], 4),
                    "fwd_ms": round(main_res["fwd_ms"], 4), "bwd_ms": round(main_res["bwd_ms"], 4),
                    "stage_ms": {k: round(v, 4) for k, v in st.items()}},
-        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+        "roofline": roof,
+        "backward": backward_rates(main_res),
+        "onbox_mfma_ceiling": onbox,
         "other_workloads": others,
     }
     if args.others:   # the extra measurements are left out of single-workload (profiling) runs

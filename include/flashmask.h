@@ -250,6 +250,22 @@ const char* flashmask_last_hip_error(void);
  */
 int flashmask_profile_events(void** events, int count);
 
+/*
+ * Measurement aid (not part of the paper's method): the matrix-core rate this chip reaches on its own.
+ * Launches `workgroups` workgroups of 4 waves that do nothing but bf16 matrix-core instructions (the
+ * 32x32x16 one the tile loops use, four independent accumulation chains per wave) on the operands given,
+ * so a benchmark can time it with events on `hip_stream` and put the tile loops' rate next to what the
+ * matrix cores deliver at the clock and power they hold by themselves (Section 5.4 of the paper quotes
+ * its kernels against a theoretical peak; this is the measured counterpart).
+ *   operands  in   device, 16 KiB of bf16 values (random values give realistic switching activity),
+ *                  16-byte aligned
+ *   sink      out  device, fp32 [workgroups * 256]
+ *   iters     in   loop trips; each trip is 32 instructions per wave
+ *   flop      out  HOST double: floating-point operations of the launch
+ */
+int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, double* flop,
+                           void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libflashmask.so")
-SOURCES = ["fm_api.hip", "fm_preprocess.hip", "fm_fwd.hip", "fm_bwd.hip"]
+SOURCES = ["fm_api.hip", "fm_preprocess.hip", "fm_fwd.hip", "fm_bwd.hip", "fm_probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -476,7 +476,10 @@ __device__ __forceinline__ bf16x8 dkdv_operand(const DkdvBases& bs, int x) {
 template <int D>
 __device__ __forceinline__ void dkdv_sync() {
   async_wait<DkdvCfg<D>::NC>();   // copies complete in order: only the tile after the next may be in flight
-  barrier_nofence();
+  // The operand ring has reads of this entry's and the next entry's stages in flight here.  The stage
+  // refilled after the barrier is the PREVIOUS entry's: its last read fed an MFMA a whole tile of
+  // steps ago, in program order, so it has long returned.
+  barrier_reads_in_flight();
 }
 
 // One 64-row tile = two 32-row blocks.  The tile's 8*NKK MFMAs form one stream
@@ -620,9 +623,10 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   static_assert(QT == 64, "the tile loop is written for two 32-row blocks per tile");
   extern __shared__ __attribute__((aligned(256))) char smem[];   // dkdv_operand relies on the alignment
 
-  const i32x4 rec = queue_take(a.order_dkdv, a.slots_dkdv, (int*)(smem + C::CNT_OFF) + 8);
-  const int unit = rec[0], i_lo = rec[1], i_hi = rec[2];
-  if (unit < 0) return;
+  // hand-off words of the unit queue: int 8 = slot of the first take, ints 12..15 = record of the next unit
+  int* qwords = (int*)(smem + C::CNT_OFF);
+  i32x4 rec = queue_take(a.order_dkdv, a.slots_dkdv, qwords + 8);
+  if (rec[0] < 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, c = lane & 31;
@@ -630,42 +634,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   const int Hk = GEN ? a.Hk : H, G = GEN ? H / Hk : 1;   // K/V heads, query heads per K/V head
   const int Nr = RAGGED ? a.N : a.Np;     // rows the tensors really have
   const int t_r = N / QT, t_c = N / C::BC;
-  const int bh = unit / t_c, j_blk = unit - bh * t_c, b = bh / Hk, hk = bh - b * Hk;   // bh counts K/V heads
-  const int k0 = j_blk * C::BC;
-  const int kw0 = k0 + wave * 32;
-  const int key = kw0 + c;  // this lane's key column
-  const int key_ld = RAGGED ? min(key, Nr - 1) : key;
-
-  const __bf16* kp = slice_ptr<D, GEN>(a.k, a.sk, b, hk, Hk, Nr);
-  const __bf16* vp = slice_ptr<D, GEN>(a.v, a.sv, b, hk, Hk, Nr);
   const int q_rs = row_stride<D, GEN>(a.sq), k_rs = row_stride<D, GEN>(a.sk), v_rs = row_stride<D, GEN>(a.sv);
   const int do_rs = row_stride<D, GEN>(a.sdo);
-
-  // What the list of live row blocks needs comes first, so that its latency is not queued
-  // behind the fragment loads below: the block's min/max values.
-  const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
-
-  // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T) and the four
-  // bounds of this lane's key, which stay in registers (Algorithm 2 loads them once per key
-  // block).  They are only waited for after the first tile copies have been issued.
-  bf16x8 kreg[NKK], vreg[NKK];
-#pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) {
-    kreg[kk] = *(const bf16x8*)(kp + (size_t)key_ld * k_rs + kk * 16 + 8 * g);
-    vreg[kk] = *(const bf16x8*)(vp + (size_t)key_ld * v_rs + kk * 16 + 8 * g);
-  }
-  int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
-  int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
-
-  f32x16 dkacc[NDB], dvacc[NDB];
-#pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      dkacc[db][r] = 0.f;
-      dvacc[db][r] = 0.f;
-    }
-
   int* list = (int*)smem;
   int* wave_cnt = (int*)(smem + C::CNT_OFF);
   const float sc = a.scale * kLog2e;
@@ -714,6 +684,45 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     e_cur = __builtin_amdgcn_readfirstlane(v_next);                                                    \
   }
 
+  // A workgroup works units off until the queues are empty (a.persistent; the launch then holds one
+  // workgroup per CU) or takes exactly one (the launch holds one workgroup per unit).
+  while (true) {
+  const int unit = rec[0], i_lo = rec[1], i_hi = rec[2];
+  const int bh = unit / t_c, j_blk = unit - bh * t_c, b = bh / Hk, hk = bh - b * Hk;   // bh counts K/V heads
+  const int k0 = j_blk * C::BC;
+  const int kw0 = k0 + wave * 32;
+  const int key = kw0 + c;  // this lane's key column
+  const int key_ld = RAGGED ? min(key, Nr - 1) : key;
+
+  const __bf16* kp = slice_ptr<D, GEN>(a.k, a.sk, b, hk, Hk, Nr);
+  const __bf16* vp = slice_ptr<D, GEN>(a.v, a.sv, b, hk, Hk, Nr);
+
+  // What the list of live row blocks needs comes first, so that its latency is not queued
+  // behind the fragment loads below: the block's min/max values.
+  const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
+
+  // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T) and the four
+  // bounds of this lane's key, which stay in registers (Algorithm 2 loads them once per key
+  // block).  They are only waited for after the first tile copies have been issued.
+  bf16x8 kreg[NKK], vreg[NKK];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    kreg[kk] = *(const bf16x8*)(kp + (size_t)key_ld * k_rs + kk * 16 + 8 * g);
+    vreg[kk] = *(const bf16x8*)(vp + (size_t)key_ld * v_rs + kk * 16 + 8 * g);
+  }
+  int b_lts = a.lts[(size_t)b * N + key], b_lte = a.lte[(size_t)b * N + key];
+  int b_uts = a.uts[(size_t)b * N + key], b_ute = a.ute[(size_t)b * N + key];
+
+  f32x16 dkacc[NDB], dvacc[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dkacc[db][r] = 0.f;
+      dvacc[db][r] = 0.f;
+    }
+  bool drawn = !a.persistent;   // the next unit's ticket has been drawn (uniform over the workgroup)
+
   // only the row blocks [i_lo, i_hi) can be live for this key block (found by the work pre-pass)
   for (int chunk = i_lo; chunk < i_hi; chunk += C::LIST_CAP) {
     int n_plain = 0;
@@ -744,6 +753,11 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
       }
       async_copy16_lanes8(my_vec + i_p * QT, lds_address(st_ + C::Q_BYTES + C::DO_BYTES) + wave * 128);
     }
+    // the next unit's ticket and record, while these copies are in flight
+    if (!drawn) {
+      if (tid == 0) queue_prefetch(a.order_dkdv, a.slots_dkdv, qwords + 12);
+      drawn = true;
+    }
     // The fragment and bound loads must be complete, and known complete to the compiler, before
     // the tile loops: a compiler-inserted wait for them inside a loop would also drain the
     // copies in flight there.  (No-op after the first chunk.)
@@ -769,7 +783,9 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     __syncthreads();   // the ring is refilled by the next head, the list rebuilt by the next chunk
     }  // query heads
   }
-#undef FM_TILE_LOOP
+  if (!drawn) {   // a unit without a live tile: nothing was in flight to hide the draw behind
+    if (tid == 0) queue_prefetch(a.order_dkdv, a.slots_dkdv, qwords + 12);
+  }
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
   __bf16* dkp = (__bf16*)slice_ptr<D, GEN>(a.dk, a.sdk, b, hk, Hk, Nr);
@@ -784,6 +800,13 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
       dkp[(size_t)krow * dk_rs + db * 32 + c] = (__bf16)(dkacc[db][r] * a.scale);
       dvp_out[(size_t)krow * dv_rs + db * 32 + c] = (__bf16)dvacc[db][r];
     }
+  if (!a.persistent) break;
+  __syncthreads();                       // the next record is in LDS (written before the tile loops, or just above)
+  rec = queue_next_record(qwords + 12);
+  if (rec[0] < 0) break;
+  __syncthreads();                       // everyone has read it before the next unit's draw overwrites it
+  }
+#undef FM_TILE_LOOP
 }
 
 }  // namespace fm
@@ -810,7 +833,9 @@ static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DqCfg<D>;
   static bool allowed[FM_MAX_DEVICES] = {};
   if (hipError_t e = fm_allow_lds((const void*)dq_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
-  hipLaunchKernelGGL((dq_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, a);
+  FmBwdArgs b = a;
+  b.persistent = false;
+  hipLaunchKernelGGL((dq_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, b);
   return hipGetLastError();
 }
 
@@ -830,8 +855,10 @@ static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DkdvCfg<D>;
   static bool allowed[FM_MAX_DEVICES] = {};
   if (hipError_t e = fm_allow_lds((const void*)dkdv_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
-  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dkdv)), dim3(256), C::LDS_BYTES, stream,
-                     a);
+  FmBwdArgs b = a;
+  b.persistent = (fm_persist_mask() & 2) != 0;
+  const int grid = b.persistent ? fm_persistent_grid(a.slots_dkdv, 1) : fm_launch_grid(a.slots_dkdv);
+  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(grid), dim3(256), C::LDS_BYTES, stream, b);
   return hipGetLastError();
 }
 

@@ -204,11 +204,23 @@ template <int N>
 __device__ __forceinline__ void async_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-// Workgroup barrier without the memory fence of __syncthreads(): the caller has
-// already waited for the async copies that must be visible, and every LDS read
-// of the buffer about to be overwritten was consumed by an MFMA before the
-// wave got here.
+// Workgroup barrier without the memory fence of __syncthreads(): the caller has already waited for
+// the async copies that must be visible.  Every LDS read of the buffer about to be overwritten must
+// have returned before the wave arrives (another wave's copy may refill it right after): the wait for
+// this wave's outstanding LDS reads is part of the barrier, so the invariant holds by construction and
+// not by where the compiler happened to place the instructions that consume the reads (the copies are
+// issued from inline assembly, so the compiler does not see them as LDS writes it must order against).
+// It costs nothing where the reads have been consumed already.
 __device__ __forceinline__ void barrier_nofence() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// The same barrier without the wait, for a point in the middle of an instruction stream that keeps LDS
+// reads in flight across it on purpose: the caller must know that none of those reads targets the buffer
+// that is refilled after the barrier.
+__device__ __forceinline__ void barrier_reads_in_flight() {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -301,27 +313,29 @@ __device__ __forceinline__ int opaque(int x) {
 // has most left, and when all are used up it gets nothing.  Returns the slot record, wave-uniform,
 // with unit = -1 for "nothing".  One barrier; lds_word is a scratch word in LDS.  The counters sit
 // behind the slot records and are zeroed by the queue-building kernel of every call.
-__device__ __forceinline__ i32x4 queue_take(int* order, int slots, int* lds_word) {
-  if (threadIdx.x == 0) {
-    int* counters = order + 4 * (size_t)slots;
-    const int per_queue = slots / FM_QUEUES;
-    int q = blockIdx.x % FM_QUEUES;
-    int t = atomicAdd(counters + q, 1);
-    for (int attempt = 0; t >= per_queue && attempt < FM_QUEUES; ++attempt) {
-      int best = -1, best_left = 0;
-      for (int g = 0; g < FM_QUEUES; ++g) {
-        const int left = per_queue - __hip_atomic_load(counters + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (left > best_left) {
-          best_left = left;
-          best = g;
-        }
+// The slot drawn by the calling thread (one thread per workgroup calls this), -1 for "nothing left".
+__device__ __forceinline__ int queue_draw(int* order, int slots) {
+  int* counters = order + 4 * (size_t)slots;
+  const int per_queue = slots / FM_QUEUES;
+  int q = blockIdx.x % FM_QUEUES;
+  int t = atomicAdd(counters + q, 1);
+  for (int attempt = 0; t >= per_queue && attempt < FM_QUEUES; ++attempt) {
+    int best = -1, best_left = 0;
+    for (int g = 0; g < FM_QUEUES; ++g) {
+      const int left = per_queue - __hip_atomic_load(counters + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (left > best_left) {
+        best_left = left;
+        best = g;
       }
-      if (best < 0) break;
-      q = best;
-      t = atomicAdd(counters + q, 1);
     }
-    *lds_word = t < per_queue ? t * FM_QUEUES + q : -1;
+    if (best < 0) break;
+    q = best;
+    t = atomicAdd(counters + q, 1);
   }
+  return t < per_queue ? t * FM_QUEUES + q : -1;
+}
+__device__ __forceinline__ i32x4 queue_take(int* order, int slots, int* lds_word) {
+  if (threadIdx.x == 0) *lds_word = queue_draw(order, slots);
   __syncthreads();
   const int slot = __builtin_amdgcn_readfirstlane(*lds_word);
   i32x4 rec = {-1, 0, 0, 0};
@@ -330,6 +344,23 @@ __device__ __forceinline__ i32x4 queue_take(int* order, int slots, int* lds_word
 #pragma unroll
     for (int e = 0; e < 4; ++e) rec[e] = __builtin_amdgcn_readfirstlane(r[e]);
   }
+  return rec;
+}
+// A workgroup that goes on to another unit after this one draws that unit's ticket ahead of time: one
+// thread calls this while the tile copies of the current unit are in flight (the atomic and the record
+// load that depends on it then cost nothing), and every thread picks the record up with
+// queue_next_record() after a barrier at the end of the unit.  lds_rec: four words of LDS.
+__device__ __forceinline__ void queue_prefetch(int* order, int slots, int* lds_rec) {
+  const int slot = queue_draw(order, slots);
+  i32x4 r = {-1, 0, 0, 0};
+  if (slot >= 0) r = *(const i32x4*)(order + 4 * (size_t)slot);
+  *(i32x4*)lds_rec = r;
+}
+__device__ __forceinline__ i32x4 queue_next_record(const int* lds_rec) {
+  const i32x4 r = *(const i32x4*)lds_rec;
+  i32x4 rec;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) rec[e] = __builtin_amdgcn_readfirstlane(r[e]);
   return rec;
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 // The tile loops draw their work units from FM_QUEUES interleaved queues (one per XCD).
 constexpr int FM_QUEUES = 8;
@@ -22,15 +23,47 @@ inline hipError_t fm_allow_lds(const void* kernel, int bytes, bool (&done)[FM_MA
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev >= 0 && dev < FM_MAX_DEVICES && done[dev]) return hipSuccess;
+  // The flags are shared by every host thread that calls the library: atomic accesses; two threads
+  // that both find a flag clear both set the attribute, which is harmless (same value).
+  if (dev >= 0 && dev < FM_MAX_DEVICES && __atomic_load_n(&done[dev], __ATOMIC_ACQUIRE)) return hipSuccess;
   e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess && dev >= 0 && dev < FM_MAX_DEVICES) done[dev] = true;
+  if (e == hipSuccess && dev >= 0 && dev < FM_MAX_DEVICES) __atomic_store_n(&done[dev], true, __ATOMIC_RELEASE);
   return e;
 }
 // Workgroups of a tile-loop launch: one per slot plus a reserve of one eighth, through which the
 // XCDs that finish their own queue early take units from the others (a workgroup that finds
 // every queue empty ends at once).
 inline int fm_launch_grid(int slots) { return slots + fm_order_slots(slots / 8); }
+// Compute units of the current device (looked up once per device), 0 on failure.
+inline int fm_compute_units() {
+  static int cached[FM_MAX_DEVICES] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= FM_MAX_DEVICES) return 0;
+  int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
+  }
+  return n;
+}
+// Workgroups of a persistent tile-loop launch (every workgroup works units off until the queues are
+// empty): what the chip holds at once, `per_cu` workgroups on each compute unit, rounded up to whole
+// rounds of the FM_QUEUES queues; never more than the one-unit-per-workgroup launch would have.
+inline int fm_persistent_grid(int slots, int per_cu) {
+  const int cus = fm_compute_units();
+  if (cus <= 0) return fm_launch_grid(slots);
+  const int g = (cus * per_cu + FM_QUEUES - 1) / FM_QUEUES * FM_QUEUES;
+  return g < fm_launch_grid(slots) ? g : fm_launch_grid(slots);
+}
+// Experiment switch while the persistent loops are being measured: FM_PERSIST=0 turns them off.
+inline int fm_persist_mask() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("FM_PERSIST");
+    v = e ? atoi(e) : 7;
+  }
+  return v;
+}
 
 // Tile shapes (rows x key columns) each pass classifies at.
 constexpr int FM_FWD_BR = 128, FM_FWD_BC = 64;
@@ -64,6 +97,11 @@ hipError_t fm_launch_row_order(const int* minmax, int B, int H, int Hk, int N, i
 hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block_r, int block_c, int* work,
                                int* range, int* order, hipStream_t stream);
 
+// Measurement aid (fm_probe.hip): `workgroups` x 4 waves each issue iters x fm_mfma_ceiling_ops_per_iter()
+// MFMAs (32x32x16 bf16) on the operands given (2 * 8 * 64 * 16 bytes), one float per thread into sink.
+hipError_t fm_launch_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream);
+int fm_mfma_ceiling_ops_per_iter();
+
 // Element strides of a bf16 tensor indexed [batch][head][row][d] (d contiguous).
 struct FmStride {
   long long b, h, n;
@@ -89,6 +127,7 @@ struct FmFwdArgs {
   bool general;
   int Hk;
   FmStride sq, sk, sv, so;
+  bool persistent;    // workgroups work units off until the queues are empty (set by the launcher)
 };
 hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream);
 
@@ -109,6 +148,7 @@ struct FmBwdArgs {
   bool general;
   int Hk;
   FmStride sq, sk, sv, so, sdo, sdq, sdk, sdv;
+  bool persistent;    // set per launch by the launchers of the dQ and dK/dV loops
 };
 hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream);
 hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream);

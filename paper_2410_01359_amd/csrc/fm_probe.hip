@@ -1,0 +1,54 @@
+// Measurement aid: the matrix-core ceiling this chip reaches on its own.
+//
+// A kernel that does nothing but v_mfma_f32_32x32x16_bf16 on caller-given (random) operands, in the
+// launch shape of the tile loops (256-thread workgroups, the whole chip filled), so that a benchmark
+// can put the tile loops' rate next to what the matrix cores deliver under their own power draw and
+// clock, not only next to the data-sheet peak.
+#include "fm_common.h"
+#include "fm_kernels.h"
+
+namespace fm {
+
+// Every wave keeps CHAINS independent accumulators going (the tile loops have two to four) and rotates
+// through NOPS operand pairs held in registers.  `operands`: 2 * NOPS * 64 lanes * 16 bytes, read once;
+// `sink`: one float per thread, written once, so that nothing is optimised away.
+template <int CHAINS, int NOPS>
+__global__ __launch_bounds__(256, 2) void mfma_ceiling_kernel(const bf16x8* __restrict__ operands, float* __restrict__ sink,
+                                                              int iters) {
+  const int lane = threadIdx.x & 63;
+  bf16x8 a[NOPS], b[NOPS];
+#pragma unroll
+  for (int i = 0; i < NOPS; ++i) {
+    a[i] = operands[(2 * i) * 64 + lane];
+    b[i] = operands[(2 * i + 1) * 64 + lane];
+  }
+  f32x16 acc[CHAINS];
+#pragma unroll
+  for (int c = 0; c < CHAINS; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < NOPS; ++i)
+#pragma unroll
+      for (int c = 0; c < CHAINS; ++c) acc[c] = mfma32(a[(i + c) % NOPS], b[i], acc[c]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < CHAINS; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[c][r];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace fm
+
+// MFMAs one wave issues per loop iteration.
+constexpr int kChains = 4, kOps = 8;
+
+hipError_t fm_launch_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream) {
+  hipLaunchKernelGGL((fm::mfma_ceiling_kernel<kChains, kOps>), dim3(workgroups), dim3(256), 0, stream,
+                     (const fm::bf16x8*)operands, sink, iters);
+  return hipGetLastError();
+}
+int fm_mfma_ceiling_ops_per_iter() { return kChains * kOps; }

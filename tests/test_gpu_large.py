@@ -104,3 +104,41 @@ def test_backward_and_table_entry_points_reject_bad_arguments():
         fm.flashmask_fwd(q, q, q, vec, vec, vec, vec, -1.0)
     with pytest.raises(fm.FlashMaskError):
         fm.flashmask_preprocess(vec, vec, vec, vec, 48)                    # block size not a multiple of 32
+
+
+def test_two_host_threads_on_two_streams_match_serial_calls():
+    """Distinct streams with distinct workspaces may be driven from different host threads at the same
+    time: forward + backward issued concurrently from two threads (different shapes, so different kernel
+    instantiations raise their LDS limits for the first time in parallel too) give the bits of serial calls."""
+    import threading
+    import paper_2410_01359_amd as fm
+    from gpu_util import to_device
+    cases = [workloads.small_workload("causal_document", 2048, seed=301, B=1, H=6, d=128),
+             workloads.small_workload("shared_question", 1500, seed=302, B=2, H=3, d=64)]
+    inputs = [to_device(w)[1:] for w in cases]
+
+    def run(idx, stream, rounds, sink):
+        w, (dev, vecs) = cases[idx], inputs[idx]
+        ws_f = torch.empty(fm.flashmask_workspace_bytes(fm.FM_PASS_FWD, w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(fm.flashmask_workspace_bytes(fm.FM_PASS_BWD, w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+        with torch.cuda.stream(stream):
+            for _ in range(rounds):
+                out, lse = fm.flashmask_fwd(dev["q"], dev["k"], dev["v"], *vecs, w.scale, workspace=ws_f)
+                grads = fm.flashmask_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], *vecs, w.scale, workspace=ws_b)
+            stream.synchronize()
+        sink[idx] = (out, lse, *grads)
+
+    serial, threaded = {}, {}
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    threads = [threading.Thread(target=run, args=(i, streams[i], 8, threaded)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for i in range(2):
+        run(i, torch.cuda.current_stream(), 1, serial)
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert len(threaded[i]) == 5
+        for a, b in zip(serial[i], threaded[i]):
+            assert torch.equal(a, b), f"case {i}"

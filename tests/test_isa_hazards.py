@@ -20,15 +20,15 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _assembly(tmp_path):
+def _assembly(tmp_path, source="fm_bwd.hip"):
     import importlib
     build = importlib.import_module("paper_2410_01359_amd.build")
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     if not (os.path.exists(hipcc) or shutil.which(hipcc)):
         pytest.skip("hipcc not available")
-    out = os.path.join(tmp_path, "fm_bwd.s")
+    out = os.path.join(tmp_path, source.replace(".hip", ".s"))
     flags = [f for f in build.FLAGS if f != "-shared"]
-    cmd = [hipcc, *flags, "--cuda-device-only", "-S", os.path.join(build.CSRC, "fm_bwd.hip"), "-o", out]
+    cmd = [hipcc, *flags, "--cuda-device-only", "-S", os.path.join(build.CSRC, source), "-o", out]
     subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE, timeout=600)
     return open(out).read()
 
@@ -75,3 +75,31 @@ def test_dkdv_inline_asm_mfma_wait_states(tmp_path):
                 continue
             assert not (_regs(l, "a") & accs), f"{name}: '{l}' touches an accumulator register"
         assert sum(1 for l in real if l == "s_nop 15") >= 3, f"{name}: drain missing"
+
+
+@pytest.mark.parametrize("source", ["fm_fwd.hip", "fm_bwd.hip"])
+def test_lds_window_register_is_written_only_by_the_copy_helpers(tmp_path, source):
+    """The tile copies (global_load_lds) take their LDS destination from M0, which the copy helpers set
+    in one inline-assembly statement (async_window) and use in later ones (async_copy16_window) without
+    the compiler knowing of the dependency.  That is sound as long as nothing the COMPILER emits writes
+    M0 in a tile-loop kernel: every write of M0, and every global_load_lds, must sit inside an
+    inline-assembly block of the generated code."""
+    asm = _assembly(str(tmp_path), source)
+    kernels = list(re.finditer(r"^(_ZN2fm\d+(?:fwd|dq|dkdv)_kernel\w+):.*?^\.Lfunc_end\d+:", asm, re.S | re.M))
+    assert len(kernels) == (8 if source == "fm_fwd.hip" else 16)
+    for m in kernels:
+        inside, copies, windows = False, 0, 0
+        for raw in m.group(0).split("\n"):
+            l = raw.strip()
+            if l.startswith(";;#ASMSTART"):
+                inside = True
+            elif l.startswith(";;#ASMEND"):
+                inside = False
+            elif l and not l.startswith(";") and not l.startswith("."):
+                writes_m0 = re.match(r"s_\w+\s+m0\b", l) is not None
+                if writes_m0:
+                    windows += 1
+                if l.startswith("global_load_lds"):
+                    copies += 1
+                assert inside or not (writes_m0 or l.startswith("global_load_lds")), f"{m.group(1)}: '{l}' outside inline assembly"
+        assert copies > 0 and windows > 0, m.group(1)
