@@ -684,6 +684,13 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     e_cur = __builtin_amdgcn_readfirstlane(v_next);                                                    \
   }
 
+  // the first unit's min/max values (Section 4.2's table); the later units' arrive with their records
+  MinMax8 gmm;
+  {
+    const int bh0 = rec[0] / t_c;
+    gmm = load_minmax(a.minmax_dkdv + (size_t)(bh0 / Hk) * 8 * t_c, t_c, rec[0] - bh0 * t_c);
+  }
+
   // A workgroup works units off until the queues are empty (a.persistent; the launch then holds one
   // workgroup per CU) or takes exactly one (the launch holds one workgroup per unit).
   while (true) {
@@ -696,10 +703,6 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
 
   const __bf16* kp = slice_ptr<D, GEN>(a.k, a.sk, b, hk, Hk, Nr);
   const __bf16* vp = slice_ptr<D, GEN>(a.v, a.sv, b, hk, Hk, Nr);
-
-  // What the list of live row blocks needs comes first, so that its latency is not queued
-  // behind the fragment loads below: the block's min/max values.
-  const MinMax8 gmm = load_minmax(a.minmax_dkdv + (size_t)b * 8 * t_c, t_c, j_blk);
 
   // K and V fragments of this wave's 32 keys (B operands of S = Q K^T, dP = dO V^T) and the four
   // bounds of this lane's key, which stay in registers (Algorithm 2 loads them once per key
@@ -755,7 +758,7 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     }
     // the next unit's ticket and record, while these copies are in flight
     if (!drawn) {
-      if (tid == 0) queue_prefetch(a.order_dkdv, a.slots_dkdv, qwords + 12);
+      if (tid == 0) queue_prefetch_key_block(a.order_dkdv, a.slots_dkdv, qwords + 12, a.minmax_dkdv, t_c, Hk);
       drawn = true;
     }
     // The fragment and bound loads must be complete, and known complete to the compiler, before
@@ -784,7 +787,7 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
     }  // query heads
   }
   if (!drawn) {   // a unit without a live tile: nothing was in flight to hide the draw behind
-    if (tid == 0) queue_prefetch(a.order_dkdv, a.slots_dkdv, qwords + 12);
+    if (tid == 0) queue_prefetch_key_block(a.order_dkdv, a.slots_dkdv, qwords + 12, a.minmax_dkdv, t_c, Hk);
   }
 
   // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
@@ -804,6 +807,8 @@ __global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
   __syncthreads();                       // the next record is in LDS (written before the tile loops, or just above)
   rec = queue_next_record(qwords + 12);
   if (rec[0] < 0) break;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) gmm.v[e] = __builtin_amdgcn_readfirstlane(qwords[16 + e]);
   __syncthreads();                       // everyone has read it before the next unit's draw overwrites it
   }
 #undef FM_TILE_LOOP

@@ -18,6 +18,9 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 #define FM_LDS __attribute__((address_space(3)))
 
+#ifndef FM_FAST_LIST
+#define FM_FAST_LIST 1
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -356,6 +359,21 @@ __device__ __forceinline__ void queue_prefetch(int* order, int slots, int* lds_r
   if (slot >= 0) r = *(const i32x4*)(order + 4 * (size_t)slot);
   *(i32x4*)lds_rec = r;
 }
+// The same for a pass whose units are key blocks: the unit's eight min/max values (Section 4.2's table,
+// row stride t_c, `kv_heads` units per batch row and key block) go into lds_rec[4..11] as well.
+__device__ __forceinline__ void queue_prefetch_key_block(int* order, int slots, int* lds_rec, const int* table, int t_c,
+                                                         int kv_heads) {
+  const int slot = queue_draw(order, slots);
+  i32x4 r = {-1, 0, 0, 0};
+  if (slot >= 0) r = *(const i32x4*)(order + 4 * (size_t)slot);
+  *(i32x4*)lds_rec = r;
+  if (r[0] >= 0) {
+    const int bh = r[0] / t_c, j = r[0] - bh * t_c, b = bh / kv_heads;
+    const MinMax8 mm = load_minmax(table + (size_t)b * 8 * t_c, t_c, j);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) lds_rec[4 + e] = mm.v[e];
+  }
+}
 __device__ __forceinline__ i32x4 queue_next_record(const int* lds_rec) {
   const i32x4 r = *(const i32x4*)lds_rec;
   i32x4 rec;
@@ -430,6 +448,24 @@ __device__ __forceinline__ int entry_need_pairs(int entry) { return (entry >> 26
 // masked ones after, each group in ascending order.
 __device__ __forceinline__ int build_live_row_blocks(const MinMax8& t, int n, int block_r, int i_begin, int i_end,
                                                      int* list, int* wave_cnt, int& n_plain) {
+  if (FM_FAST_LIST && i_end - i_begin <= 64) {
+    // Short range (a sliding window, a small document): one wave's lanes cover it, so every wave forms
+    // the same two ballots and wave 0 writes the list; one barrier instead of four.
+    const int lane = threadIdx.x & 63;
+    const int i = i_begin + lane;
+    int cls = T_FULLY;
+    if (i < i_end) cls = classify_tile(i * block_r, min((i + 1) * block_r, n), t);
+    const unsigned long long plain = __ballot(cls == T_UNMASKED), part = __ballot((cls & T_PARTIAL) != 0);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int np = __popcll(plain);
+    if (threadIdx.x < 64) {
+      if (cls == T_UNMASKED) list[__popcll(plain & below)] = i | (cls << 24);
+      if (cls & T_PARTIAL) list[np + __popcll(part & below)] = i | (cls << 24);
+    }
+    __syncthreads();
+    n_plain = np;
+    return np + __popcll(part);
+  }
   int running = 0;
 #pragma unroll 1
   for (int pass = 0; pass < 2; ++pass) {
