@@ -209,6 +209,37 @@ def mfma_ceiling(torch, fm, hip, iters=4000, reps=5):
             "kernel": "v_mfma_f32_32x32x16_bf16 only, random operands, 2048 workgroups x 4 waves, 4 chains per wave"}
 
 
+def atomic_ceiling(torch, fm, hip, reps=4):
+    """Rate of the dQ update as Algorithm 2's column-parallel loop would issue it (a 64 x 128 fp32 block per
+    tile, no-return atomic adds into HBM), and the cap it would put on a backward that fuses dQ into the
+    dK/dV loop: one such block per 64 x 128-key tile, whose five matrix products are 10 d FLOP per score
+    element."""
+    heads, n_tiles, tiles, wgs = 8, 512, 64, 2048
+    acc = torch.zeros((heads, n_tiles, 64, 128), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    fm.flashmask_atomic_ceiling(acc, 4, wgs)
+    torch.cuda.synchronize()
+    ev = make_events(hip, 2)
+    best = None
+    for _ in range(reps):
+        hip.hipEventRecord(ev[0], ctypes.c_void_p(stream))
+        nbytes = fm.flashmask_atomic_ceiling(acc, tiles, wgs)
+        hip.hipEventRecord(ev[1], ctypes.c_void_p(stream))
+        hip.hipEventSynchronize(ev[1])
+        ms = elapsed(hip, ev[0], ev[1])
+        best = ms if best is None else min(best, ms)
+    for e in ev:
+        hip.hipEventDestroy(e)
+    tbs = nbytes / best / 1e9
+    d = 128
+    cap = tbs * 1e12 / (64 * 128 * 4) * (10.0 * d * 64 * 128) / 1e12
+    return {"fp32_atomic_add_TBps": round(tbs, 3), "ms": round(best, 4),
+            "pattern": "2048 workgroups x 64 tiles of 64 x 128 fp32, 8 heads x 32768 rows, a head's adds from one XCD",
+            "fused_dq_backward_cap_tflops": round(cap, 1),
+            "note": "cap on a backward that adds dQ per 64 x 128-key tile from the column-parallel loop (10 d FLOP per element, d = 128)"}
+
+
 def forward_only_grouped(torch, fm, orc, workloads, steps):
     """Forward pass alone at the head configuration of the paper's inference appendix (32 query
     heads on 8 K/V heads, d = 128, batch 1) under a causal-document mask of 16 equal documents at
@@ -317,8 +348,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, help="1, 2, 3, 4a, 4b or 5")
-    ap.add_argument("--others", default="2,3,4a,4b", help="extra workloads reported in `other_workloads` ('' = none)")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, help="1, 2, 3, 4a, 4b, 5 or 4b-d64")
+    ap.add_argument("--others", default="2,3,4a,4b,4b-d64",
+                    help="extra workloads reported in `other_workloads` ('' = none); 4b-d64 = run 4b at d = 64, 32 heads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=12288)
     ap.add_argument("--sweep", action="store_true",
@@ -328,6 +360,8 @@ def main():
                          "kernel-speed tables (128K tokens, 32 heads, N = 8K / 32K / 128K)")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="only measure the on-box matrix-core ceiling (an MFMA-only kernel) and print it")
+    ap.add_argument("--atomic-ceiling", action="store_true",
+                    help="only measure the fp32 atomic-add rate of a dQ update fused into the dK/dV loop and print it")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (read once, written once): a kernel of known "
                          "HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -350,6 +384,10 @@ def main():
 
     if args.mfma_ceiling:
         print(json.dumps(mfma_ceiling(torch, fm, hip)), flush=True)
+        return
+
+    if args.atomic_ceiling:
+        print(json.dumps(atomic_ceiling(torch, fm, hip)), flush=True)
         return
 
     if args.sweep:
@@ -415,6 +453,7 @@ def main():
     }
     if args.others:   # the extra measurements are left out of single-workload (profiling) runs
         line["forward_only_grouped_heads"] = forward_only_grouped(torch, fm, orc, workloads, max(5, args.steps))
+        line["dq_atomic_ceiling"] = atomic_ceiling(torch, fm, hip)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, orc, workloads, args.cpu_rows)
     print(json.dumps(line), flush=True)

@@ -266,6 +266,19 @@ int flashmask_profile_events(void** events, int count);
 int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, double* flop,
                            void* hip_stream);
 
+/*
+ * Measurement aid (not part of the paper's method): the rate at which this chip takes the dQ update of
+ * Algorithm 2 as the paper's column-parallel loop issues it -- every tile of the loop adds a 64 x 128
+ * fp32 block into dQ in HBM.  `workgroups` workgroups each add `tiles` such blocks into
+ *   acc  in/out  device fp32 [heads][n_tiles][64][128] (zero it first if the sums matter)
+ * with no-return fp32 atomic adds, a head's adds all coming from one XCD.  A benchmark times the launch
+ * with events; `bytes` (HOST double) receives the bytes of fp32 updates issued.  The backward here
+ * computes dQ in a second, row-parallel loop instead, because this rate caps a fused loop far below
+ * the matrix-core rate.
+ */
+int flashmask_atomic_ceiling(float* acc, int heads, int n_tiles, int tiles, int workgroups, double* bytes,
+                              void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

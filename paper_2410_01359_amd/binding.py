@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.flashmask_last_hip_error.argtypes = []
     lib.flashmask_mfma_ceiling.restype = i
     lib.flashmask_mfma_ceiling.argtypes = [vp, fp, i, i, ctypes.POINTER(ctypes.c_double), vp]
+    lib.flashmask_atomic_ceiling.restype = i
+    lib.flashmask_atomic_ceiling.argtypes = [fp, i, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
     lib.flashmask_profile_events.restype = i
     lib.flashmask_profile_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), i]
     _LIB = lib
@@ -266,6 +268,18 @@ def flashmask_mfma_ceiling(operands: torch.Tensor, sink: torch.Tensor, workgroup
     _check(load_library().flashmask_mfma_ceiling(operands.data_ptr(), sink.data_ptr(), workgroups, iters,
                                                  ctypes.byref(flop), _stream()), "flashmask_mfma_ceiling")
     return float(flop.value)
+
+
+def flashmask_atomic_ceiling(acc: torch.Tensor, tiles: int, workgroups: int) -> float:
+    """Enqueue the atomic-add measurement kernel on acc (fp32 [heads, n_tiles, 64, 128]); returns the bytes of
+    fp32 updates it issues."""
+    _dev(acc, torch.float32, "acc")
+    if acc.dim() != 4 or tuple(acc.shape[2:]) != (64, 128):
+        raise FlashMaskError("acc must be [heads, n_tiles, 64, 128]")
+    nbytes = ctypes.c_double(0.0)
+    _check(load_library().flashmask_atomic_ceiling(acc.data_ptr(), acc.shape[0], acc.shape[1], tiles, workgroups,
+                                                   ctypes.byref(nbytes), _stream()), "flashmask_atomic_ceiling")
+    return float(nbytes.value)
 
 
 def flashmask_unit_queues(pass_id: int, lts, lte, uts, ute, H: int, d: int) -> torch.Tensor:

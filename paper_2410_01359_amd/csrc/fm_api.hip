@@ -133,6 +133,17 @@ int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, in
   return e == hipSuccess ? FM_OK : hip_fail(e);
 }
 
+int flashmask_atomic_ceiling(float* acc, int heads, int n_tiles, int tiles, int workgroups, double* bytes,
+                              void* hip_stream) {
+  if (!acc || !bytes) return FM_ERR_NULL;
+  if (heads <= 0 || n_tiles <= 0 || tiles <= 0 || workgroups <= 0 || workgroups > (1 << 20) || tiles > (1 << 20))
+    return FM_ERR_ARG;
+  if ((long long)heads * n_tiles >= (1ll << 31) / (64 * 128)) return FM_ERR_SHAPE;
+  *bytes = 4.0 * 64 * 128 * (double)tiles * workgroups;
+  hipError_t e = fm_launch_atomic_ceiling(acc, n_tiles, tiles, heads, workgroups, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FM_OK : hip_fail(e);
+}
+
 int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c) {
   if (!block_r || !block_c) return FM_ERR_NULL;
   if (d != 64 && d != 128) return FM_ERR_SHAPE;

@@ -101,6 +101,9 @@ hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block
 // MFMAs (32x32x16 bf16) on the operands given (2 * 8 * 64 * 16 bytes), one float per thread into sink.
 hipError_t fm_launch_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream);
 int fm_mfma_ceiling_ops_per_iter();
+// Measurement aid: `workgroups` workgroups each add `tiles` 64 x 128 fp32 tiles into acc
+// ([heads][n_tiles][64][128] floats) with no-return atomic adds.
+hipError_t fm_launch_atomic_ceiling(float* acc, int n_tiles, int tiles, int heads, int workgroups, hipStream_t stream);
 
 // Element strides of a bf16 tensor indexed [batch][head][row][d] (d contiguous).
 struct FmStride {

@@ -41,7 +41,34 @@ __global__ __launch_bounds__(256, 2) void mfma_ceiling_kernel(const bf16x8* __re
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// What accumulating dQ from the column-parallel loop, as Algorithm 2 writes it, would cost on this chip:
+// every workgroup adds `tiles` tiles of 64 x 128 fp32 (one per 64-row x 128-key tile of the dK/dV loop) into
+// a [heads][n_tiles][64][128] accumulator with no-return fp32 atomic adds, in the register layout the dK/dV
+// loop would hold such a tile in (32 adds of 64 lanes per wave and tile).  A head's adds all come from
+// workgroups of one XCD (workgroup x works on head x % heads), as the unit queues would arrange it.
+__global__ __launch_bounds__(256) void atomic_ceiling_kernel(float* __restrict__ acc, int n_tiles, int tiles, int heads) {
+  const int x = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  float* base = acc + (size_t)(x % heads) * n_tiles * 64 * 128;
+  for (int t = 0; t < tiles; ++t) {
+    float* tp = base + (size_t)(((x / 8) * 2 + t) % n_tiles) * 64 * 128;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 32 * (w & 1) + 8 * (r >> 2) + 4 * g + (r & 3);
+        const int col = 64 * (w >> 1) + 32 * db + c;
+        unsafeAtomicAdd(tp + row * 128 + col, (float)(r + db));
+      }
+  }
+}
+
 }  // namespace fm
+
+hipError_t fm_launch_atomic_ceiling(float* acc, int n_tiles, int tiles, int heads, int workgroups, hipStream_t stream) {
+  hipLaunchKernelGGL(fm::atomic_ceiling_kernel, dim3(workgroups), dim3(256), 0, stream, acc, n_tiles, tiles, heads);
+  return hipGetLastError();
+}
 
 // MFMAs one wave issues per loop iteration.
 constexpr int kChains = 4, kOps = 8;

@@ -76,6 +76,13 @@ def _golden_rows():
     return rows
 
 
+def _eviction_times(n):
+    """Every other key (at random) is evicted at a random later row, the rest never: no 128-key block is
+    ever evicted as a whole, which is what the printed Random Eviction rows (equal to Causal) imply."""
+    rng = np.random.Generator(np.random.PCG64(n))
+    return np.where(rng.random(n) < 0.5, n, np.arange(n) + 1 + rng.integers(0, n, size=n))
+
+
 @pytest.mark.parametrize("mask,n,bh,fw,bw,rho", _golden_rows())
 def test_paper_printed_sparsity_and_tflops(mask, n, bh, fw, bw, rho):
     """Tile counter + FLOP model reproduce the figures printed in the paper's
@@ -83,7 +90,9 @@ def test_paper_printed_sparsity_and_tflops(mask, n, bh, fw, bw, rho):
     vec = {"full": lambda: workloads.full_mask(n),
            "causal": lambda: workloads.causal_mask(n),
            "sliding_window": lambda: workloads.sliding_window_mask(n, n // 16),
-           "prefix_lm": lambda: workloads.prefix_lm_mask(n, n // 2)}[mask]()
+           "prefix_lm": lambda: workloads.prefix_lm_mask(n, n // 2),
+           "global_sliding_window": lambda: workloads.global_sliding_window_mask(n, 128, n // 16),
+           "random_eviction": lambda: workloads.random_eviction_mask(n, _eviction_times(n))}[mask]()
     cls = orc.classify_tiles_fast(orc.minmax_tables(*vec, 128), n, 128, 128)
     got_rho = orc.block_sparsity(cls)
     assert abs(got_rho - rho) <= 0.0051, (got_rho, rho)

@@ -295,6 +295,12 @@ def config(name: str) -> Workload:
         w = Workload("4b", 1, 16, 32768, 128, BASE_SEED + 401, "prefix_lm")
         w.structure = [{"prefix": 4096}]
         w.vectors = [prefix_lm_mask(w.N, 4096)]
+    elif name == "4b-d64":
+        # not one of the five configurations: run (b) of configuration 4 at head dimension 64 with twice the
+        # heads (same hidden size, same FLOPs), the shape of the paper's d = 64 kernel tables
+        w = Workload("4b-d64", 1, 32, 32768, 64, BASE_SEED + 402, "prefix_lm")
+        w.structure = [{"prefix": 4096}]
+        w.vectors = [prefix_lm_mask(w.N, 4096)]
     elif name == "5":
         w = Workload("5", 1, 8, 131072, 128, BASE_SEED + 500, "causal_document")
         rng = _mask_rng(w.seed)
