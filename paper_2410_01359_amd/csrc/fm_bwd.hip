@@ -309,8 +309,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 // four bounds of that key sit in four registers for the whole kernel and P^T,
 // dS^T are already A operands of dV += P^T dO and dK += dS^T Q.
 //
-// One wave per SIMD (the accumulators alone take 128 registers), so the
-// overlap of matrix and vector work is arranged inside the wave: a 64-row tile
+// One wave per SIMD at d = 128 (the accumulators alone take 128 registers; at d = 64 they take 64 and
+// two workgroups share a CU), so the overlap of matrix and vector work is arranged inside the wave: a 64-row tile
 // is two 32-row blocks, and the instruction stream is
 //   S0,dP0 | S1,dP1 with the exp/dS arithmetic of block 0 between the MFMAs |
 //   dV,dK of block 0 with the arithmetic of block 1 between the MFMAs | dV,dK of block 1
@@ -545,10 +545,18 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
         pb[qb] = mfma32(op[x % RD], vreg[kk], pb[qb]);
     } else {
       const int u = x - 2 * NST, qb = u / NST, w = u % NST, h = w / (2 * NDB), db = (w % (2 * NDB)) / 2;
-      if (u & 1)
+      if (D == 64) {
+        // d = 64: the accumulators are half as many and two workgroups share a CU (two waves per SIMD,
+        // 256 registers each), so they stay ordinary compiler-managed registers
+        if (u & 1)
+          dkacc[db] = mfma32(dsa[qb][h], op[x % RD], dkacc[db]);
+        else
+          dvacc[db] = mfma32(pa[qb][h], op[x % RD], dvacc[db]);
+      } else if (u & 1) {
         mfma32_acc(dkacc[db], dsa[qb][h], op[x % RD], db == 0);   // db == 0: first reader of dsa[qb][h]
-      else
+      } else {
         mfma32_acc(dvacc[db], pa[qb][h], op[x % RD], db == 0);    // ... of pa[qb][h]
+      }
     }
     // --- the workgroup step and the copies behind it
     if (x == XS) {
@@ -617,7 +625,7 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
 // walks the query heads that share it one after the other (same list of live row blocks: the
 // mask does not depend on the head), accumulating dK and dV over all of them.
 template <int D, bool RAGGED, bool GEN>
-__global__ __launch_bounds__(256, 1) void dkdv_kernel(FmBwdArgs a) {
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a) {
   using C = DkdvCfg<D>;
   constexpr int QT = C::QT, NDB = D / 32, NKK = D / 16;
   static_assert(QT == 64, "the tile loop is written for two 32-row blocks per tile");
@@ -862,7 +870,7 @@ static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
   if (hipError_t e = fm_allow_lds((const void*)dkdv_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
   FmBwdArgs b = a;
   b.persistent = (fm_persist_mask() & 2) != 0;
-  const int grid = b.persistent ? fm_persistent_grid(a.slots_dkdv, 1) : fm_launch_grid(a.slots_dkdv);
+  const int grid = b.persistent ? fm_persistent_grid(a.slots_dkdv, D == 64 ? 2 : 1) : fm_launch_grid(a.slots_dkdv);
   hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(grid), dim3(256), C::LDS_BYTES, stream, b);
   return hipGetLastError();
 }

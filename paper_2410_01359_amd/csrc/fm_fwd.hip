@@ -206,7 +206,7 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
 // computed but not stored.
 // GEN: tensors with caller-given strides and fewer K/V heads than query heads (see FmFwdArgs).
 template <int D, bool RAGGED, bool GEN>
-__global__ __launch_bounds__(256, 2) void fwd_kernel(FmFwdArgs a) {
+__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) {
   using C = FwdCfg<D>;
   constexpr int KT = C::KT, NKB = KT / 32, NDB = D / 32, NKK = D / 16;
   extern __shared__ __attribute__((aligned(16))) char smem[];
