@@ -699,8 +699,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
     gmm = load_minmax(a.minmax_dkdv + (size_t)(bh0 / Hk) * 8 * t_c, t_c, rec[0] - bh0 * t_c);
   }
 
-  // A workgroup works units off until the queues are empty (a.persistent; the launch then holds one
-  // workgroup per CU) or takes exactly one (the launch holds one workgroup per unit).
+  // A workgroup works units off until the queues are empty: the launch holds as many workgroups as the
+  // chip runs at once, and the next unit's ticket, record and min/max values are fetched while the first
+  // tile copies of the current unit are in flight.
   while (true) {
   const int unit = rec[0], i_lo = rec[1], i_hi = rec[2];
   const int bh = unit / t_c, j_blk = unit - bh * t_c, b = bh / Hk, hk = bh - b * Hk;   // bh counts K/V heads
@@ -732,7 +733,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
       dkacc[db][r] = 0.f;
       dvacc[db][r] = 0.f;
     }
-  bool drawn = !a.persistent;   // the next unit's ticket has been drawn (uniform over the workgroup)
+  bool drawn = false;   // the next unit's ticket has been drawn (uniform over the workgroup)
 
   // only the row blocks [i_lo, i_hi) can be live for this key block (found by the work pre-pass)
   for (int chunk = i_lo; chunk < i_hi; chunk += C::LIST_CAP) {
@@ -811,7 +812,6 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
       dkp[(size_t)krow * dk_rs + db * 32 + c] = (__bf16)(dkacc[db][r] * a.scale);
       dvp_out[(size_t)krow * dv_rs + db * 32 + c] = (__bf16)dvacc[db][r];
     }
-  if (!a.persistent) break;
   __syncthreads();                       // the next record is in LDS (written before the tile loops, or just above)
   rec = queue_next_record(qwords + 12);
   if (rec[0] < 0) break;
@@ -846,9 +846,7 @@ static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DqCfg<D>;
   static bool allowed[FM_MAX_DEVICES] = {};
   if (hipError_t e = fm_allow_lds((const void*)dq_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
-  FmBwdArgs b = a;
-  b.persistent = false;
-  hipLaunchKernelGGL((dq_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, b);
+  hipLaunchKernelGGL((dq_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots_dq)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
@@ -868,10 +866,9 @@ static hipError_t launch_dkdv_t(const FmBwdArgs& a, hipStream_t stream) {
   using C = DkdvCfg<D>;
   static bool allowed[FM_MAX_DEVICES] = {};
   if (hipError_t e = fm_allow_lds((const void*)dkdv_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
-  FmBwdArgs b = a;
-  b.persistent = (fm_persist_mask() & 2) != 0;
-  const int grid = b.persistent ? fm_persistent_grid(a.slots_dkdv, D == 64 ? 2 : 1) : fm_launch_grid(a.slots_dkdv);
-  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(grid), dim3(256), C::LDS_BYTES, stream, b);
+  // persistent: as many workgroups as the chip holds at once (one per CU at d = 128, two at d = 64)
+  const int grid = fm_persistent_grid(a.slots_dkdv, D == 64 ? 2 : 1);
+  hipLaunchKernelGGL((dkdv_kernel<D, RAGGED, GEN>), dim3(grid), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 

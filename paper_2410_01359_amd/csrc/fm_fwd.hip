@@ -384,9 +384,7 @@ static hipError_t launch_fwd_t(const FmFwdArgs& a, hipStream_t stream) {
   using C = FwdCfg<D>;
   static bool allowed[FM_MAX_DEVICES] = {};
   if (hipError_t e = fm_allow_lds((const void*)fwd_kernel<D, RAGGED, GEN>, C::LDS_BYTES, allowed); e != hipSuccess) return e;
-  FmFwdArgs b = a;
-  b.persistent = false;
-  hipLaunchKernelGGL((fwd_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots)), dim3(256), C::LDS_BYTES, stream, b);
+  hipLaunchKernelGGL((fwd_kernel<D, RAGGED, GEN>), dim3(fm_launch_grid(a.slots)), dim3(256), C::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 

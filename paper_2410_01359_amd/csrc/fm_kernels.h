@@ -2,7 +2,6 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 // The tile loops draw their work units from FM_QUEUES interleaved queues (one per XCD).
 constexpr int FM_QUEUES = 8;
@@ -55,16 +54,6 @@ inline int fm_persistent_grid(int slots, int per_cu) {
   const int g = (cus * per_cu + FM_QUEUES - 1) / FM_QUEUES * FM_QUEUES;
   return g < fm_launch_grid(slots) ? g : fm_launch_grid(slots);
 }
-// Experiment switch while the persistent loops are being measured: FM_PERSIST=0 turns them off.
-inline int fm_persist_mask() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("FM_PERSIST");
-    v = e ? atoi(e) : 7;
-  }
-  return v;
-}
-
 // Tile shapes (rows x key columns) each pass classifies at.
 constexpr int FM_FWD_BR = 128, FM_FWD_BC = 64;
 constexpr int FM_DQ_BR = 128, FM_DQ_BC = 64;
@@ -130,7 +119,6 @@ struct FmFwdArgs {
   bool general;
   int Hk;
   FmStride sq, sk, sv, so;
-  bool persistent;    // workgroups work units off until the queues are empty (set by the launcher)
 };
 hipError_t fm_launch_fwd(const FmFwdArgs& a, hipStream_t stream);
 
@@ -151,7 +139,6 @@ struct FmBwdArgs {
   bool general;
   int Hk;
   FmStride sq, sk, sv, so, sdo, sdq, sdk, sdv;
-  bool persistent;    // set per launch by the launchers of the dQ and dK/dV loops
 };
 hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream);
 hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream);
