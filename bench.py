@@ -87,13 +87,13 @@ def run_workload(name, steps, warmup, torch, fm, orc, workloads, hip, with_event
             lib.flashmask_profile_events(ev_f, 3)
         out, lse = fm.flashmask_fwd(t["q"], t["k"], t["v"], *vecs, w.scale, workspace=ws)
         if ev_b is not None:
-            lib.flashmask_profile_events(ev_b, 5)
+            lib.flashmask_profile_events(ev_b, 4)
         fm.flashmask_bwd(t["q"], t["k"], t["v"], out, lse, t["dout"], *vecs, w.scale, workspace=ws)
 
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    evs = [(make_events(hip, 3), make_events(hip, 5)) for _ in range(steps)] if with_events else [(None, None)] * steps
+    evs = [(make_events(hip, 3), make_events(hip, 4)) for _ in range(steps)] if with_events else [(None, None)] * steps
     t0 = time.perf_counter()
     for ev_f, ev_b in evs:
         step(ev_f, ev_b)
@@ -104,17 +104,16 @@ def run_workload(name, steps, warmup, torch, fm, orc, workloads, hip, with_event
     res = {"workload": name, "ms_per_step": wall_ms, "tflops": f_total / wall_ms / 1e9, "block_sparsity": rho,
            "unmasked_tflop": f_total / 1e12, "tile_tflop": f_tile / 1e12, "workload_obj": w}
     if with_events:
-        stage = {"fwd_setup": [], "fwd_tiles": [], "bwd_setup": [], "bwd_dvec": [], "bwd_dkdv": [], "bwd_dq": []}
+        stage = {"fwd_setup": [], "fwd_tiles": [], "bwd_setup": [], "bwd_dq": [], "bwd_dkdv": []}
         fwd_ms, bwd_ms = [], []
         for ev_f, ev_b in evs:
             stage["fwd_setup"].append(elapsed(hip, ev_f[0], ev_f[1]))
             stage["fwd_tiles"].append(elapsed(hip, ev_f[1], ev_f[2]))
             stage["bwd_setup"].append(elapsed(hip, ev_b[0], ev_b[1]))
-            stage["bwd_dvec"].append(elapsed(hip, ev_b[1], ev_b[2]))
+            stage["bwd_dq"].append(elapsed(hip, ev_b[1], ev_b[2]))       # includes the D pre-pass (its prologue)
             stage["bwd_dkdv"].append(elapsed(hip, ev_b[2], ev_b[3]))
-            stage["bwd_dq"].append(elapsed(hip, ev_b[3], ev_b[4]))
             fwd_ms.append(elapsed(hip, ev_f[0], ev_f[2]))
-            bwd_ms.append(elapsed(hip, ev_b[0], ev_b[4]))
+            bwd_ms.append(elapsed(hip, ev_b[0], ev_b[3]))
         res["stage_ms"] = {k: float(np.mean(v)) for k, v in stage.items()}
         res["fwd_ms"], res["bwd_ms"] = float(np.mean(fwd_ms)), float(np.mean(bwd_ms))
         # algorithmic FLOPs of each tile loop per launch: matrix products per tile x 2*d per unmasked element

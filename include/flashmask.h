@@ -243,8 +243,8 @@ const char* flashmask_last_hip_error(void);
  * flashmask_fwd / flashmask_bwd call records them on its stream between its
  * internal launches, so a benchmark can time one kernel inside the call:
  *   forward : [0] entry, [1] after preprocessing + unit queues, [2] after the tile loop
- *   backward: [0] entry, [1] after preprocessing + unit queues, [2] after the
- *             D pre-pass, [3] after the dK/dV loop, [4] after the dQ loop
+ *   backward: [0] entry, [1] after preprocessing + unit queues, [2] after the dQ loop (whose
+ *             prologue is the D pre-pass), [3] after the dK/dV loop
  * The array must stay valid until cleared with (NULL, 0).  Process-global and
  * not thread-safe; entries that are NULL or beyond `count` are skipped.
  */

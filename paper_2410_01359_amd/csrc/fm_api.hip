@@ -368,15 +368,14 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* out
   e = fm_launch_bwd_setup(lts, lte, uts, ute, B, H, Hk, Np, rows, cols, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(1, stream);
-  e = fm_launch_dvec(a, stream);
+  // the dQ loop first: its prologue is also Algorithm 2's D pre-pass and leaves -D and the log2-domain
+  // lse of every row in the workspace for the dK/dV loop
+  e = fm_launch_bwd_dq(a, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(2, stream);
   e = fm_launch_bwd_dkdv(a, stream);
   if (e != hipSuccess) return hip_fail(e);
   mark(3, stream);
-  e = fm_launch_bwd_dq(a, stream);
-  if (e != hipSuccess) return hip_fail(e);
-  mark(4, stream);
   return FM_OK;
 }
 

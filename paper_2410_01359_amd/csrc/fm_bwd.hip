@@ -1,11 +1,12 @@
-// Backward pass (Algorithm 2) for gfx950, as three kernels:
+// Backward pass (Algorithm 2) for gfx950, as two kernels:
 //
-//   dvec_kernel   D_i = sum_c dO_ic O_ic                       (Algorithm 2, D pre-pass)
+//   dq_kernel     row-parallel loop over query blocks i, run first: its prologue is Algorithm 2's D
+//                 pre-pass, D_i = sum_c dO_ic O_ic (left in the workspace for the other loop); then
+//                 S, P = exp(S - L), dP, dS per tile and dQ_i += dS K_j, accumulated in registers in a
+//                 fixed order.
 //   dkdv_kernel   column-parallel loop over key blocks j: recompute S and
 //                 P = exp(S - L), dV_j += P^T dO_i, dP = dO_i V_j^T,
 //                 dS = P o (dP - D_i), dK_j += dS^T Q_i           (Algorithm 2 main loop)
-//   dq_kernel     row-parallel loop over query blocks i: the same S, P, dP, dS
-//                 and dQ_i += dS K_j, accumulated in registers in a fixed order.
 //
 // Algorithm 2 adds every tile's dS K_j into dQ_i in HBM from the column-parallel
 // loop.  On this chip fp32 atomic adds sustain about 1.4 TB/s, which would cap
@@ -15,44 +16,6 @@
 #include "fm_kernels.h"
 
 namespace fm {
-
-// ---------------------------------------------------------------------------
-// D pre-pass: writes -D_i = -sum_c dO_ic O_ic (plus the log2-domain copy of lse the tile loops use).  One row per
-// 16 (d = 128) or 8 (d = 64) lanes, 16 bytes per lane.
-// ---------------------------------------------------------------------------
-template <int D, bool GEN>
-__global__ __launch_bounds__(256) void dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
-                                                   const float* __restrict__ lse, float* __restrict__ dvec,
-                                                   float* __restrict__ lse2, long long slices, int heads, int n, int np,
-                                                   FmStride so, FmStride sdo) {
-  constexpr int LPR = D / 8;  // lanes per row
-  const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long prow = gid / LPR;              // row index in the padded [slices][np] layout
-  const int part = (int)(gid % LPR);
-  const long long bh = prow / np;
-  const int r = (int)(prow % np);
-  const bool real = bh < slices && r < n;        // rows r >= n are the padding of a ragged sequence
-  const long long row = bh * n + r;
-  float acc = 0.f;
-  if (real) {
-    const long long b = bh / heads, h = bh - b * heads;
-    const __bf16* orow = GEN ? out + b * so.b + h * so.h + (long long)r * so.n : out + row * D;
-    const __bf16* grow = GEN ? dout + b * sdo.b + h * sdo.h + (long long)r * sdo.n : dout + row * D;
-    const bf16x8 o = *(const bf16x8*)(orow + part * 8);
-    const bf16x8 g = *(const bf16x8*)(grow + part * 8);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc += (float)o[e] * (float)g[e];
-  }
-#pragma unroll
-  for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (bh < slices && part == 0) {
-    dvec[prow] = -acc;   // stored negated: the tile loops add it (0 in the padding)
-    // lse for the backward's exponent: log2 domain, and +inf for a row with no visible key
-    // (lse = -inf) and for padding rows, so that exp2(s - lse2) is exactly 0 there
-    const float l = real ? lse[row] : -INFINITY;
-    lse2[prow] = (l == -INFINITY) ? INFINITY : l * kLog2e;
-  }
-}
 
 // ---------------------------------------------------------------------------
 // dQ: row-parallel, same transposed-score layout as the forward kernel.
@@ -124,9 +87,32 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     qreg[kk] = *(const bf16x8*)(qp + (size_t)row_ld * q_rs + kk * 16 + 8 * g);
     doreg[kk] = *(const bf16x8*)(dop + (size_t)row_ld * do_rs + kk * 16 + 8 * g);
   }
-  // lse in the log2 domain (+inf for a row with no visible key, so that P = 0 there)
-  float lse2 = a.lse2[(size_t)bh * N + row];
-  float dneg = a.dvec[(size_t)bh * N + row];   // -D of this lane's row
+  // Algorithm 2's D pre-pass, folded into this loop's prologue (the dO fragments are at hand; the O
+  // fragments are loaded in the same layout): D_i = sum_c dO_ic O_ic of this lane's row, a partial sum
+  // per lane and one exchange with the lane that holds the other half of the row.  -D and the log2-domain
+  // lse (+inf for a row with no visible key and for padding rows, so that P = 0 there) also go to the
+  // workspace, where the dK/dV loop, which runs after this one, picks them up per tile.
+  const bool real_row = !RAGGED || row < Nr;
+  float lse2 = real_row ? a.lse[(size_t)bh * Nr + row] : -INFINITY;
+  float dneg = 0.f;
+  {
+    const __bf16* outp = slice_ptr<D, GEN>(a.out, a.so, b, h, H, Nr);
+    const int o_rs = row_stride<D, GEN>(a.so);
+    bf16x8 oreg[NKK];
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) oreg[kk] = *(const bf16x8*)(outp + (size_t)row_ld * o_rs + kk * 16 + 8 * g);
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dneg -= (float)oreg[kk][e] * (float)doreg[kk][e];
+    dneg += partner32(dneg);
+    if (!real_row) dneg = 0.f;
+  }
+  lse2 = (lse2 == -INFINITY) ? INFINITY : lse2 * kLog2e;
+  if (g == 0) {
+    a.dvec[(size_t)bh * N + row] = dneg;
+    a.lse2[(size_t)bh * N + row] = lse2;
+  }
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
     settle(qreg[kk]);
@@ -825,21 +811,6 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
 }  // namespace fm
 
 using namespace fm;
-
-template <int D, bool GEN>
-static hipError_t launch_dvec_t(const FmBwdArgs& a, hipStream_t stream) {
-  const long long slices = (long long)a.B * a.H;
-  const long long threads = slices * a.Np * (D / 8);
-  const unsigned blocks = (unsigned)((threads + 255) / 256);
-  hipLaunchKernelGGL((dvec_kernel<D, GEN>), dim3(blocks), dim3(256), 0, stream, (const __bf16*)a.out,
-                     (const __bf16*)a.dout, a.lse, a.dvec, a.lse2, slices, a.H, a.N, a.Np, a.so, a.sdo);
-  return hipGetLastError();
-}
-
-hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream) {
-  if (a.d == 128) return a.general ? launch_dvec_t<128, true>(a, stream) : launch_dvec_t<128, false>(a, stream);
-  return a.general ? launch_dvec_t<64, true>(a, stream) : launch_dvec_t<64, false>(a, stream);
-}
 
 template <int D, bool RAGGED, bool GEN>
 static hipError_t launch_dq_t(const FmBwdArgs& a, hipStream_t stream) {

@@ -130,8 +130,9 @@ struct FmBwdArgs {
   int* order_dq;           // queue slots and counters of the dQ pass (live key-block range per row block)
   const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
   int* order_dkdv;         // queue slots and counters of the dK/dV pass (live row-block range per key block)
-  float* dvec;             // -D = -rowsum(dO o O), [B,H,Np] (stored negated; 0 in the padding)
-  float* lse2;             // lse * log2(e), +inf where lse = -inf and in the padding, [B,H,Np]
+  float* dvec;             // -D = -rowsum(dO o O), [B,H,Np] (stored negated; 0 in the padding): written by the
+                           // dQ loop's prologue, read by the dK/dV loop
+  float* lse2;             // lse * log2(e), +inf where lse = -inf and in the padding, [B,H,Np]: likewise
   void *dq, *dk, *dv;
   float scale;
   int B, H, N, Np, d;
@@ -140,6 +141,5 @@ struct FmBwdArgs {
   int Hk;
   FmStride sq, sk, sv, so, sdo, sdq, sdk, sdv;
 };
-hipError_t fm_launch_dvec(const FmBwdArgs& a, hipStream_t stream);
 hipError_t fm_launch_bwd_dq(const FmBwdArgs& a, hipStream_t stream);
 hipError_t fm_launch_bwd_dkdv(const FmBwdArgs& a, hipStream_t stream);
