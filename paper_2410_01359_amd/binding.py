@@ -67,7 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.flashmask_last_hip_error.restype = ctypes.c_char_p
     lib.flashmask_last_hip_error.argtypes = []
     lib.flashmask_mfma_ceiling.restype = i
-    lib.flashmask_mfma_ceiling.argtypes = [vp, fp, i, i, ctypes.POINTER(ctypes.c_double), vp]
+    lib.flashmask_mfma_ceiling.argtypes = [vp, fp, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
     lib.flashmask_atomic_ceiling.restype = i
     lib.flashmask_atomic_ceiling.argtypes = [fp, i, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
     lib.flashmask_profile_events.restype = i
@@ -258,14 +258,15 @@ def flashmask_bwd_ex(q, k, v, out, lse, dout, lts, lte, uts, ute, scale: float,
     return dq, dk, dv
 
 
-def flashmask_mfma_ceiling(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int) -> float:
+def flashmask_mfma_ceiling(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int,
+                           shape: int = 0) -> float:
     """Enqueue the matrix-core-only measurement kernel; returns the floating-point operations it performs."""
     _dev(operands, torch.bfloat16, "operands")
     _dev(sink, torch.float32, "sink")
     if operands.numel() < 8192 or sink.numel() < workgroups * 256:
         raise FlashMaskError("operands needs 8192 bf16 values, sink workgroups * 256 floats")
     flop = ctypes.c_double(0.0)
-    _check(load_library().flashmask_mfma_ceiling(operands.data_ptr(), sink.data_ptr(), workgroups, iters,
+    _check(load_library().flashmask_mfma_ceiling(operands.data_ptr(), sink.data_ptr(), workgroups, iters, shape,
                                                  ctypes.byref(flop), _stream()), "flashmask_mfma_ceiling")
     return float(flop.value)
 

@@ -123,13 +123,14 @@ int flashmask_profile_events(void** events, int count) {
   return FM_OK;
 }
 
-int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, double* flop,
+int flashmask_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, int shape, double* flop,
                            void* hip_stream) {
   if (!operands || !sink || !flop) return FM_ERR_NULL;
-  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24)) return FM_ERR_ARG;
+  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24) || shape < 0 || shape > 2)
+    return FM_ERR_ARG;
   if (misaligned(operands)) return FM_ERR_ALIGN;
   *flop = 2.0 * 32 * 32 * 16 * (double)fm_mfma_ceiling_ops_per_iter() * iters * 4.0 * workgroups;
-  hipError_t e = fm_launch_mfma_ceiling(operands, sink, workgroups, iters, (hipStream_t)hip_stream);
+  hipError_t e = fm_launch_mfma_ceiling(operands, sink, workgroups, iters, shape, (hipStream_t)hip_stream);
   return e == hipSuccess ? FM_OK : hip_fail(e);
 }
 

@@ -87,8 +87,11 @@ hipError_t fm_launch_col_order(const int* minmax, int B, int H, int N, int block
                                int* range, int* order, hipStream_t stream);
 
 // Measurement aid (fm_probe.hip): `workgroups` x 4 waves each issue iters x fm_mfma_ceiling_ops_per_iter()
-// MFMAs (32x32x16 bf16) on the operands given (2 * 8 * 64 * 16 bytes), one float per thread into sink.
-hipError_t fm_launch_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream);
+// MFMA slots (shape 0: one 32x32x16 bf16 instruction; 1: two of the 16x16x32 shape, the same floating-point
+// operations; 2: shape 0 plus the forward loop's side work per MFMA) on the operands given
+// (2 * 8 * 64 * 16 bytes), one float per thread into sink.
+hipError_t fm_launch_mfma_ceiling(const void* operands, float* sink, int workgroups, int iters, int shape,
+                                  hipStream_t stream);
 int fm_mfma_ceiling_ops_per_iter();
 // Measurement aid: `workgroups` workgroups each add `tiles` 64 x 128 fp32 tiles into acc
 // ([heads][n_tiles][64][128] floats) with no-return atomic adds.
