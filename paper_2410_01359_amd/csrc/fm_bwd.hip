@@ -275,7 +275,11 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 
   __bf16* dqp = (__bf16*)slice_ptr<D, GEN>(a.dq, a.sdq, b, h, H, Nr);
   const int dq_rs = row_stride<D, GEN>(a.sdq);
-  if (RAGGED && row >= Nr) return;
+  // every wave is past its last tile and nothing is in flight into the stages (the barrier that ends a
+  // pass over the list): their first bytes serve as the waves' store staging
+  using RSt = RowStage<D>;
+  static_assert(4 * RSt::BYTES <= 2 * C::STAGE, "store staging fits the stages");
+  char* stage = smem + C::STAGE_OFF + wave * RSt::BYTES;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -283,8 +287,9 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
       bf16x4 o4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(dqacc[db][rq * 4 + e] * a.scale);
-      *(bf16x4*)(dqp + (size_t)row * dq_rs + db * 32 + 8 * rq + 4 * g) = o4;
+      RSt::put(stage, c, g, db, rq, o4);
     }
+  RSt::flush(stage, dqp + (size_t)qw0 * dq_rs, dq_rs, lane, RAGGED ? min(32, Nr - qw0) : 32);
 }
 
 // ---------------------------------------------------------------------------
@@ -535,13 +540,13 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
         // d = 64: the accumulators are half as many and two workgroups share a CU (two waves per SIMD,
         // 256 registers each), so they stay ordinary compiler-managed registers
         if (u & 1)
-          dkacc[db] = mfma32(dsa[qb][h], op[x % RD], dkacc[db]);
+          dkacc[db] = mfma32(op[x % RD], dsa[qb][h], dkacc[db]);
         else
-          dvacc[db] = mfma32(pa[qb][h], op[x % RD], dvacc[db]);
+          dvacc[db] = mfma32(op[x % RD], pa[qb][h], dvacc[db]);
       } else if (u & 1) {
-        mfma32_acc(dkacc[db], dsa[qb][h], op[x % RD], db == 0);   // db == 0: first reader of dsa[qb][h]
+        mfma32_acc(dkacc[db], op[x % RD], dsa[qb][h], db == 0);   // db == 0: first reader of dsa[qb][h]
       } else {
-        mfma32_acc(dvacc[db], pa[qb][h], op[x % RD], db == 0);    // ... of pa[qb][h]
+        mfma32_acc(dvacc[db], op[x % RD], pa[qb][h], db == 0);    // ... of pa[qb][h]
       }
     }
     // --- the workgroup step and the copies behind it
@@ -683,6 +688,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
   {
     const int bh0 = rec[0] / t_c;
     gmm = load_minmax(a.minmax_dkdv + (size_t)(bh0 / Hk) * 8 * t_c, t_c, rec[0] - bh0 * t_c);
+    // into scalar registers here, once: left in vector registers, every unit's list build would wait for
+    // "these loads" again, i.e. for everything the workgroup has in flight, the previous unit's result
+    // stores included
+#pragma unroll
+    for (int e = 0; e < 8; ++e) gmm.v[e] = __builtin_amdgcn_readfirstlane(gmm.v[e]);
   }
 
   // A workgroup works units off until the queues are empty: the launch holds as many workgroups as the
@@ -785,19 +795,34 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
     if (tid == 0) queue_prefetch_key_block(a.order_dkdv, a.slots_dkdv, qwords + 12, a.minmax_dkdv, t_c, Hk);
   }
 
-  // accumulators: register r of block db holds [key kw0 + 8*(r/4) + 4*g + r%4][d = db*32 + c]
+  // accumulators (dK^T, dV^T): register r of block db holds [d = db*32 + 8*(r/4) + 4*g + r%4][key kw0 + c].
+  // Nothing is in flight into the ring here and every wave is past its last tile (the barrier that ends the
+  // loop over heads and chunks), so the ring's first bytes serve as the waves' store staging.
   __bf16* dkp = (__bf16*)slice_ptr<D, GEN>(a.dk, a.sdk, b, hk, Hk, Nr);
   __bf16* dvp_out = (__bf16*)slice_ptr<D, GEN>(a.dv, a.sdv, b, hk, Hk, Nr);
   const int dk_rs = row_stride<D, GEN>(a.sdk), dv_rs = row_stride<D, GEN>(a.sdv);
+  {
+    using RSt = RowStage<D>;
+    static_assert(8 * RSt::BYTES <= C::NSTAGE * C::STAGE, "store staging fits the ring");
+    char* stage_k = smem + C::STAGE_OFF + (2 * wave) * RSt::BYTES;
+    char* stage_v = stage_k + RSt::BYTES;
 #pragma unroll
-  for (int db = 0; db < NDB; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int krow = kw0 + 8 * (r >> 2) + 4 * g + (r & 3);
-      if (RAGGED && krow >= Nr) continue;
-      dkp[(size_t)krow * dk_rs + db * 32 + c] = (__bf16)(dkacc[db][r] * a.scale);
-      dvp_out[(size_t)krow * dv_rs + db * 32 + c] = (__bf16)dvacc[db][r];
-    }
+      for (int q = 0; q < 4; ++q) {
+        bf16x4 k4, v4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          k4[e] = (__bf16)(dkacc[db][4 * q + e] * a.scale);
+          v4[e] = (__bf16)dvacc[db][4 * q + e];
+        }
+        RSt::put(stage_k, c, g, db, q, k4);
+        RSt::put(stage_v, c, g, db, q, v4);
+      }
+    const int n_rows = RAGGED ? min(32, Nr - kw0) : 32;
+    RSt::flush(stage_k, dkp + (size_t)kw0 * dk_rs, dk_rs, lane, n_rows);
+    RSt::flush(stage_v, dvp_out + (size_t)kw0 * dv_rs, dv_rs, lane, n_rows);
+  }
   __syncthreads();                       // the next record is in LDS (written before the tile loops, or just above)
   rec = queue_next_record(qwords + 12);
   if (rec[0] < 0) break;

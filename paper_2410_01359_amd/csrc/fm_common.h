@@ -280,6 +280,32 @@ __device__ __forceinline__ void tile_load_async_clamped(const __bf16* tensor_bh,
   }
 }
 
+// Result stores.  The tile loops end with a 32-row x D result per wave held rows-on-lanes: lane (c, g)
+// (c = lane % 32, g = lane / 32) has, of row c, the four consecutive elements 32 db + 8 q + 4 g .. +3 for
+// every (db, q).  Stored from there, one instruction would touch 32 rows with 16 bytes each.  Each wave
+// instead passes its block through a private piece of LDS (rows RS bytes apart: D bf16 plus 16 bytes, so
+// that the 8-byte deposits of 32 rows spread over all banks) and writes whole rows, 16 bytes per lane.
+// No barrier: a wave reads only what it wrote itself, and LDS serves a wave's accesses in order.
+template <int D>
+struct RowStage {
+  static constexpr int RS = 2 * D + 16;
+  static constexpr int BYTES = 32 * RS;   // per wave and result
+  static constexpr int LPR = D / 8;       // lanes per row when every lane moves 16 bytes
+  static constexpr int RPI = 64 / LPR;    // rows per store instruction
+  static __device__ __forceinline__ void put(char* stage, int c, int g, int db, int q, bf16x4 v) {
+    *(bf16x4*)(stage + c * RS + (32 * db + 8 * q + 4 * g) * 2) = v;
+  }
+  // rows [0, n_rows) of the block go to row0, row0 + row_stride, ... (elements)
+  static __device__ __forceinline__ void flush(const char* stage, __bf16* row0, int row_stride, int lane, int n_rows) {
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+      const int r = i * RPI + lane / LPR, col = (lane % LPR) * 16;
+      const u32x4 v = *(const u32x4*)(stage + r * RS + col);
+      if (r < n_rows) *(u32x4*)((char*)(row0 + (size_t)r * row_stride) + col) = v;
+    }
+  }
+};
+
 // Where a (batch, head) slice of a tensor starts and how far its rows are apart, in elements:
 // taken from the stride record in the general instantiations, compile-time otherwise.
 template <int D, bool GEN>
@@ -385,13 +411,13 @@ __device__ __forceinline__ i32x4 queue_next_record(const int* lds_rec) {
 // Ordered compaction shared by the tile loops: every thread of a 256-thread
 // workgroup offers one candidate per pass (live or not, with its list entry);
 // live entries are appended to list[] in candidate order.  `running` carries
-// the count across passes.  Contains two barriers.
+// the count across passes.  Contains two barriers (LDS only: no wait for global memory).
 __device__ __forceinline__ void append_live(bool live, int entry, int* list, int* wave_cnt, int& running) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const unsigned long long ballot = __ballot(live);
   const int prefix = __popcll(ballot & ((1ull << lane) - 1ull));
   if (lane == 0) wave_cnt[wave] = __popcll(ballot);
-  __syncthreads();
+  barrier_nofence();   // only LDS is exchanged: the callers' global loads stay in flight across the list build
   int off = running, tot = 0;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
@@ -401,7 +427,7 @@ __device__ __forceinline__ void append_live(bool live, int entry, int* list, int
   }
   if (live) list[off + prefix] = entry;
   running += tot;
-  __syncthreads();
+  barrier_nofence();
 }
 
 // Row-parallel loops: classify key blocks [j_begin, j_end) against the
@@ -462,7 +488,7 @@ __device__ __forceinline__ int build_live_row_blocks(const MinMax8& t, int n, in
       if (cls == T_UNMASKED) list[__popcll(plain & below)] = i | (cls << 24);
       if (cls & T_PARTIAL) list[np + __popcll(part & below)] = i | (cls << 24);
     }
-    __syncthreads();
+    barrier_nofence();   // LDS only: the unit's K / V fragment loads stay in flight
     n_plain = np;
     return np + __popcll(part);
   }

@@ -360,18 +360,22 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) 
     const float lt = l_run + partner32(l_run);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int row = qw0 + c;
-    if (!RAGGED || row < Nr) {
+    // every wave is past its last tile and nothing is in flight into the K / V stages (the barrier that
+    // ends a pass over the list): their first bytes serve as the waves' store staging
+    using RSt = RowStage<D>;
+    static_assert(4 * RSt::BYTES <= C::LDS_BYTES - C::K_OFF, "store staging fits the K / V stages");
+    char* stage = smem + C::K_OFF + wave * RSt::BYTES;
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          bf16x4 o4;
+      for (int rq = 0; rq < 4; ++rq) {
+        bf16x4 o4;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][rq * 4 + e] * inv);
-          *(bf16x4*)(op + (size_t)row * o_rs + db * 32 + 8 * rq + 4 * g) = o4;
-        }
-      if (g == 0) lp[row] = lt > 0.f ? (m_run + fast_log2(lt)) * kLn2 : -INFINITY;
-    }
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][rq * 4 + e] * inv);
+        RSt::put(stage, c, g, db, rq, o4);
+      }
+    RSt::flush(stage, op + (size_t)qw0 * o_rs, o_rs, lane, RAGGED ? min(32, Nr - qw0) : 32);
+    if ((!RAGGED || row < Nr) && g == 0) lp[row] = lt > 0.f ? (m_run + fast_log2(lt)) * kLn2 : -INFINITY;
   }
 }
 
