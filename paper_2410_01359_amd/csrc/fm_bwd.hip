@@ -156,14 +156,18 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, j_hi), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
-    const int first_entry = __builtin_amdgcn_readfirstlane(list[0]);
-    FM_LOAD_TILE(first_entry, 0);
+    // the entries of tiles t and t + 1 travel in scalar registers; the one that joins them at the next tile is
+    // read from the list at the top of a tile and picked up behind the tile's barrier, so that no tile starts by
+    // waiting for LDS
+    int entry = __builtin_amdgcn_readfirstlane(list[0]);
+    int next_entry = __builtin_amdgcn_readfirstlane(list[min(1, n_live - 1)]);
+    FM_LOAD_TILE(entry, 0);
     async_wait<0>();
     barrier_nofence();
 
     for (int t = 0; t < n_live; ++t) {
-      const int entry = __builtin_amdgcn_readfirstlane(list[t]);
-      const int next_entry = __builtin_amdgcn_readfirstlane((t + 1 < n_live) ? list[t + 1] : 0);
+      const int v_after = list[min(t + 2, n_live - 1)];
+      __builtin_amdgcn_sched_barrier(0);
       if (t + 1 < n_live) FM_LOAD_TILE(next_entry, (t + 1) & 1);
 
       const char* st = smem + C::STAGE_OFF + (t & 1) * C::STAGE;
@@ -268,6 +272,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
 
       async_wait<0>();   // the next tile has landed ...
       barrier_nofence(); // ... for every wave, and every wave is done reading this one
+      entry = next_entry;
+      next_entry = __builtin_amdgcn_readfirstlane(v_after);
     }
     __syncthreads();     // the list is rebuilt by the next pass
   }

@@ -300,9 +300,10 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) 
   // end of the list are clamped to the last one; what is computed from them is never used.
 #define FM_STEP(T, CUR, NXT)                                                                     \
   {                                                                                              \
-    const int e_t = __builtin_amdgcn_readfirstlane(list[T]);                                     \
-    const int e_1 = __builtin_amdgcn_readfirstlane(list[min((T) + 1, n_live - 1)]);              \
-    const int e_2 = __builtin_amdgcn_readfirstlane(list[min((T) + 2, n_live - 1)]);              \
+    /* the list entry that joins the window at the next step: read now, picked up behind the  */ \
+    /* step's barrier, so that no step starts by waiting for LDS                               */ \
+    const int v_3 = list[min((T) + 3, n_live - 1)];                                              \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
     FM_LOAD_K(e_2, (T) & 1);                                                                     \
     FM_LOAD_V(e_1, ((T) + 1) & 1);                                                               \
     const char* vs_ = smem + C::V_OFF + ((T) & 1) * C::VSTAGE;                                   \
@@ -311,6 +312,9 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) 
                 entry_wave_class(e_t, wave) != T_UNMASKED ? entry_need_pairs(e_t) : 0, w);       \
     async_wait<0>();   /* K(T+2) and V(T+1) have landed ... */                                   \
     barrier_nofence(); /* ... for every wave, and every wave is done with K(T+1) and V(T) */     \
+    e_t = e_1;                                                                                   \
+    e_1 = e_2;                                                                                   \
+    e_2 = __builtin_amdgcn_readfirstlane(v_3);                                                   \
   }
 
   // only the key blocks [j_lo, j_hi) can be live for this row block (found by the work pre-pass)
@@ -318,11 +322,13 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) 
     const int n_live = build_live_key_blocks(table, t_c, chunk, min(chunk + C::LIST_CAP, j_hi), q0, min(q0 + C::BR, N),
                                              C::BR / 4, list, wave_cnt);
     if (n_live == 0) continue;
+    // the entries of tiles T, T + 1, T + 2 of the step about to run (clamped to the last one)
+    int e_t = __builtin_amdgcn_readfirstlane(list[0]);
+    int e_1 = __builtin_amdgcn_readfirstlane(list[min(1, n_live - 1)]);
+    int e_2 = __builtin_amdgcn_readfirstlane(list[min(2, n_live - 1)]);
     {
-      const int e_0 = __builtin_amdgcn_readfirstlane(list[0]);
-      const int e_1 = __builtin_amdgcn_readfirstlane(list[min(1, n_live - 1)]);
-      FM_LOAD_K(e_0, 0);
-      FM_LOAD_V(e_0, 0);
+      FM_LOAD_K(e_t, 0);
+      FM_LOAD_V(e_t, 0);
       FM_LOAD_K(e_1, 1);
       async_wait<0>();
       barrier_nofence();
