@@ -346,6 +346,11 @@ __device__ __forceinline__ constexpr int dkdv_vec_off(int r, bool d_part) {
 }
 
 #define FM_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Steps between the last MFMA of a block's S / dP chains and the first vector instruction that reads their
+// result: with none, that instruction waits out the MFMA's passes with the wave idle (one wave per SIMD).
+#ifndef FM_DKDV_VSHIFT
+#define FM_DKDV_VSHIFT 1
+#endif
 
 // exp / dS arithmetic of elements [e0, e0 + cnt) of one 32x32 block held in the
 // MFMA output layout: register r is query row 8*(r/4) + 4*g + r%4 of the block.
@@ -582,12 +587,13 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
       op[x % RD] = dkdv_operand<D>(bs_cur, x + RD);
     else
       op[x % RD] = dkdv_operand<D>(bs_next, x + RD - NX);
-    // --- vector work riding along.  Vector step j = x - NST - stage handles EPS elements of
-    //     block j / NST: stage A at x, stage B one step later, stage C two steps later.
+    // --- vector work riding along.  Vector step j handles EPS elements of
+    //     block j / NST: stage A at x, stage B one step later, stage C two steps later
+    //     (j = x - NST - FM_DKDV_VSHIFT - stage).
     if (x == NST - 1) vec_group(0, 0);
 #pragma unroll
     for (int stage = 2; stage >= 0; --stage) {
-      const int j = x - NST - stage;
+      const int j = x - NST - FM_DKDV_VSHIFT - stage;
       if (j >= 0 && j < 2 * NST) {
         const int qb = j / NST, e0 = (j % NST) * EPS;
         if (stage == 0) {
