@@ -297,15 +297,16 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) 
       async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::V_BYTES));                            \
   }
   // One iteration: tile T with scores in CUR, scores of tile T + 1 into NXT.  Entries past the
-  // end of the list are clamped to the last one; what is computed from them is never used.
+  // end of the list are clamped to the last one: nothing is copied for them, and the scores the last
+  // step computes from the stale K stage are never used.
 #define FM_STEP(T, CUR, NXT)                                                                     \
   {                                                                                              \
     /* the list entry that joins the window at the next step: read now, picked up behind the  */ \
     /* step's barrier, so that no step starts by waiting for LDS                               */ \
     const int v_3 = list[min((T) + 3, n_live - 1)];                                              \
     __builtin_amdgcn_sched_barrier(0);                                                           \
-    FM_LOAD_K(e_2, (T) & 1);                                                                     \
-    FM_LOAD_V(e_1, ((T) + 1) & 1);                                                               \
+    if ((T) + 2 < n_live) FM_LOAD_K(e_2, (T) & 1);                                               \
+    if ((T) + 1 < n_live) FM_LOAD_V(e_1, ((T) + 1) & 1);                                         \
     const char* vs_ = smem + C::V_OFF + ((T) & 1) * C::VSTAGE;                                   \
     fwd_step<D>(CUR, NXT, oacc, qreg, m_run, l_run, smem + C::K_OFF + (((T) + 1) & 1) * C::K_BYTES, vs_, \
                 (const int*)(vs_ + C::V_BYTES),                                                  \
