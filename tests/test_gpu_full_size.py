@@ -1,12 +1,12 @@
 """GPU: EVERY element at the full benchmark sizes, in the launch configuration bench.py times.
 
 Three kinds of evidence, none of them sampled:
-  * configs 2, 3, 4a, 4b: whole heads against the dense fp64 oracle (every element of out, lse, dq,
-    dk, dv); config 5: one whole head, taken in groups of documents (the oracle itself shows that the
+  * configs 2, 3, 4a, 4b and run 4b at d = 64: whole heads against the dense fp64 oracle (every element of
+    out, lse, dq, dk, dv); config 5: one whole head, taken in groups of documents (the oracle itself shows that the
     rows of a group send nothing to the key columns outside it);
-  * configs 2, 4a, 4b, 5, every head: the closed forms of uniform attention (Q = 0, then K = 0 with
+  * configs 2, 4a, 4b (d = 128 and d = 64), 5, every head: the closed forms of uniform attention (Q = 0, then K = 0 with
     random Q), built from the task structure in O(N d^2) without any N x N work (closed_forms.py);
-  * all five multi-tile configs: head 0's tensors copied into every head give bit-identical results in
+  * all five multi-tile configs and run 4b at d = 64: head 0's tensors copied into every head give bit-identical results in
     every head (and equal to head 0 of the ordinary run), so what the oracle shows for one head holds
     for the unit-to-head mapping of all of them.
 """
@@ -41,7 +41,7 @@ def gpu_results(name):
 def whole_head_cases():
     cases = []
     for name, heads in (("2", (0, 5, 11, 16, 21, 26, 31)), ("3", (0, 5, 11, 16, 21, 26, 31)),
-                        ("4a", (0, 8, 15)), ("4b", (0, 8, 15))):
+                        ("4a", (0, 8, 15)), ("4b", (0, 8, 15)), ("4b-d64", (0, 31))):
         for b in range(2 if name == "2" else 1):
             for h in heads:
                 cases.append((name, b, h))
@@ -96,7 +96,7 @@ def test_config5_whole_head_by_document_groups(rows):
 
 
 @pytest.mark.parametrize("zero", ["q", "k"])
-@pytest.mark.parametrize("name", ["2", "4a", "4b", "5"])
+@pytest.mark.parametrize("name", ["2", "4a", "4b", "4b-d64", "5"])
 def test_uniform_attention_closed_forms_every_head_every_element(name, zero):
     """Q = 0 (then K = 0 with the seeded Q): every score is 0, P is uniform over the visible keys, and
     all five outputs have closed forms as prefix sums over the document / window / prefix structure.
@@ -130,7 +130,7 @@ def test_uniform_attention_closed_forms_every_head_every_element(name, zero):
             check_bwd(bf16_to_np(dk[b, h]), rdk, "dk", what)
 
 
-@pytest.mark.parametrize("name", ["2", "3", "4a", "4b", "5"])
+@pytest.mark.parametrize("name", ["2", "3", "4a", "4b", "4b-d64", "5"])
 def test_replicated_heads_are_bit_identical(name):
     """Head 0 of batch row 0 copied into every head, and batch row 0's mask into every batch row: every
     (batch row, head) must then produce the same bits (each unit's arithmetic is fixed; only the queue,
