@@ -151,7 +151,7 @@ int flashmask_tile_shape(int pass, int d, int* block_r, int* block_c) {
   switch (pass) {
     case FM_PASS_FWD: *block_r = FM_FWD_BR; *block_c = FM_FWD_BC; return FM_OK;
     case FM_PASS_BWD_DKDV: *block_r = FM_DKDV_BR; *block_c = FM_DKDV_BC; return FM_OK;
-    case FM_PASS_BWD_DQ: *block_r = FM_DQ_BR; *block_c = FM_DQ_BC; return FM_OK;
+    case FM_PASS_BWD_DQ: *block_r = FM_DQ_BR; *block_c = fm_dq_bc(d); return FM_OK;
     default: return FM_ERR_ARG;
   }
 }
@@ -162,7 +162,7 @@ size_t flashmask_workspace_bytes(int pass, int B, int H, int N, int d) {
   const size_t pad = padded_bounds_bytes(B, N);
   if (pass == FM_PASS_FWD) return pad + pass_space(B, H, Np, FM_FWD_BR, FM_FWD_BC, true, 0).total;
   if (pass == FM_PASS_BWD) {
-    const PassSpace dq = pass_space(B, H, Np, FM_DQ_BR, FM_DQ_BC, true, 0);
+    const PassSpace dq = pass_space(B, H, Np, FM_DQ_BR, fm_dq_bc(d), true, 0);
     const PassSpace kv = pass_space(B, H, Np, FM_DKDV_BR, FM_DKDV_BC, false, dq.total);
     return pad + kv.total + 2 * align_up((size_t)B * H * Np * 4, 256);  // + D vector + log2-domain lse
   }
@@ -246,7 +246,7 @@ int flashmask_unit_queues(int pass, const int32_t* lts, const int32_t* lte, cons
   if (pass != FM_PASS_FWD && pass != FM_PASS_BWD_DQ && pass != FM_PASS_BWD_DKDV) return FM_ERR_ARG;
   const bool rows = pass != FM_PASS_BWD_DKDV;
   const int br = pass == FM_PASS_FWD ? FM_FWD_BR : rows ? FM_DQ_BR : FM_DKDV_BR;
-  const int bc = pass == FM_PASS_FWD ? FM_FWD_BC : rows ? FM_DQ_BC : FM_DKDV_BC;
+  const int bc = pass == FM_PASS_FWD ? FM_FWD_BC : rows ? fm_dq_bc(d) : FM_DKDV_BC;
   const int Np = padded_len(N);
   *slots = fm_order_slots(B * H * (Np / (rows ? br : bc)));
   if (!records) return FM_OK;   // size query
@@ -341,7 +341,7 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* out
     lts = padded; lte = padded + plane; uts = padded + 2 * plane; ute = padded + 3 * plane;
     ws += padded_bounds_bytes(B, N);
   }
-  const PassSpace sq = pass_space(B, H, Np, FM_DQ_BR, FM_DQ_BC, true, 0);
+  const PassSpace sq = pass_space(B, H, Np, FM_DQ_BR, fm_dq_bc(d), true, 0);
   const PassSpace skv = pass_space(B, H, Np, FM_DKDV_BR, FM_DKDV_BC, false, sq.total);   // sized for H >= Hk heads
   FmBwdArgs a;
   a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
@@ -362,7 +362,7 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* out
     a.sq = a.so = a.sdo = a.sdq = dense(H, N, d);
     a.sk = a.sv = a.sdk = a.sdv = dense(Hk, N, d);
   }
-  const FmSetup rows{FM_DQ_BR, FM_DQ_BC, (int*)(ws + sq.minmax), (int*)(ws + sq.work), (int*)(ws + sq.range),
+  const FmSetup rows{FM_DQ_BR, fm_dq_bc(d), (int*)(ws + sq.minmax), (int*)(ws + sq.work), (int*)(ws + sq.range),
                      (int*)(ws + sq.order)};
   const FmSetup cols{FM_DKDV_BR, FM_DKDV_BC, (int*)(ws + skv.minmax), (int*)(ws + skv.work), (int*)(ws + skv.range),
                      (int*)(ws + skv.order)};

@@ -22,7 +22,7 @@ namespace fm {
 // ---------------------------------------------------------------------------
 template <int D>
 struct DqCfg {
-  static constexpr int KT = FM_DQ_BC;
+  static constexpr int KT = fm_dq_bc(D);
   static constexpr int BR = FM_DQ_BR;
   using L = TileLayout<D>;
   static constexpr int K_BYTES = KT * L::RS;
@@ -66,15 +66,17 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   const int q_rs = row_stride<D, GEN>(a.sq), k_rs = row_stride<D, GEN>(a.sk), v_rs = row_stride<D, GEN>(a.sv);
   const int do_rs = row_stride<D, GEN>(a.sdo);
   const int* table = a.minmax_dq + (size_t)b * 8 * t_c;
-  // lanes of wave 0 copy the four bound slices of a partially masked tile
+  // The four bound slices of a partially masked tile (KT ints each, one after the other in LDS) are copied by the
+  // first BND_WAVES waves, 1 KB each: a lane moves 16 bytes of vector (64 * wave + lane) / (KT / 4).
+  constexpr int BND_LPV = KT / 4, BND_WAVES = 4 * BND_LPV / 64;
   const int* my_bvec;
   {
-    const int which = lane >> 4;
+    const int which = (64 * wave + lane) / BND_LPV;
     const int* p = a.lts;
     if (which == 1) p = a.lte;
     if (which == 2) p = a.uts;
     if (which == 3) p = a.ute;
-    my_bvec = p + (size_t)b * N + (lane & 15) * 4;
+    my_bvec = p + (size_t)b * N + (lane % BND_LPV) * 4;
   }
   CopyLanes<D> copy_lanes, copy_lanes_v_;
   copy_lanes.init(lane, 2 * k_rs);
@@ -140,15 +142,19 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
   {                                                                                            \
     const int j_ = entry_block(ENTRY, chunk);                                                  \
     char* st_ = smem + C::STAGE_OFF + (BUF) * C::STAGE;                                        \
-    if (RAGGED && (j_ + 1) * KT > Nr) {                                                        \
-      tile_load_async_clamped<D>(kp, j_ * KT, Nr, st_, wave, lane, 2 * k_rs);                  \
-      tile_load_async_clamped<D>(vp, j_ * KT, Nr, st_ + C::K_BYTES, wave, lane, 2 * v_rs);     \
-    } else {                                                                                   \
-      tile_load_async<D>(kp + (size_t)j_ * KT * k_rs, copy_lanes, st_, wave, 2 * k_rs);        \
-      tile_load_async<D>(vp + (size_t)j_ * KT * v_rs, copy_lanes_v, st_ + C::K_BYTES, wave, 2 * v_rs); \
+    _Pragma("unroll") for (int sub = 0; sub < KT / 64; ++sub) {   /* 64 keys per copy call */  \
+      const int r_ = j_ * KT + sub * 64;                                                       \
+      char* ks_ = st_ + sub * 64 * C::L::RS;                                                   \
+      if (RAGGED && r_ + 64 > Nr) {                                                            \
+        tile_load_async_clamped<D>(kp, r_, Nr, ks_, wave, lane, 2 * k_rs);                     \
+        tile_load_async_clamped<D>(vp, r_, Nr, ks_ + C::K_BYTES, wave, lane, 2 * v_rs);        \
+      } else {                                                                                 \
+        tile_load_async<D>(kp + (size_t)r_ * k_rs, copy_lanes, ks_, wave, 2 * k_rs);           \
+        tile_load_async<D>(vp + (size_t)r_ * v_rs, copy_lanes_v, ks_ + C::K_BYTES, wave, 2 * v_rs); \
+      }                                                                                        \
     }                                                                                          \
-    if (entry_tile_class(ENTRY) == T_PARTIAL && wave == 0)                                     \
-      async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES));             \
+    if (entry_tile_class(ENTRY) == T_PARTIAL && wave < BND_WAVES)                              \
+      async_copy16(my_bvec + j_ * KT, lds_address(st_ + C::K_BYTES + C::V_BYTES) + wave * 1024); \
   }
 
   // only the key blocks [j_lo, j_hi) can be live for this row block (found by the work pre-pass)

@@ -56,7 +56,10 @@ inline int fm_persistent_grid(int slots, int per_cu) {
 }
 // Tile shapes (rows x key columns) each pass classifies at.
 constexpr int FM_FWD_BR = 128, FM_FWD_BC = 64;
-constexpr int FM_DQ_BR = 128, FM_DQ_BC = 64;
+constexpr int FM_DQ_BR = 128;
+// Key columns per tile of the dQ pass: at d = 64 a 128-key tile has the bytes (and the MFMAs) of a 64-key tile at
+// d = 128, so that a tile's fixed work (copies' set-up, list entry, wait, barrier) is spread over as much math.
+constexpr int fm_dq_bc(int d) { return d == 64 ? 128 : 64; }
 constexpr int FM_DKDV_BR = 64, FM_DKDV_BC = 128;
 
 // One pass's setup buffers (in the workspace) and tile shape.
@@ -129,7 +132,7 @@ struct FmBwdArgs {
   const void *q, *k, *v, *out, *dout;
   const float* lse;
   const int *lts, *lte, *uts, *ute;
-  const int* minmax_dq;    // [B][8][T_c] at FM_DQ_BC
+  const int* minmax_dq;    // [B][8][T_c] at fm_dq_bc(d)
   int* order_dq;           // queue slots and counters of the dQ pass (live key-block range per row block)
   const int* minmax_dkdv;  // [B][8][T_c] at FM_DKDV_BC
   int* order_dkdv;         // queue slots and counters of the dK/dV pass (live row-block range per key block)
