@@ -367,17 +367,19 @@ __device__ __forceinline__ constexpr int dkdv_vec_off(int r, bool d_part) {
 //   A: t = s*sc - lse2 (with the element mask)     B: p = exp2(t)     C: dS = p * (dP - D)
 // (dP - D comes straight out of the MFMA: its accumulator starts from the -D values of the rows)
 // Register r of a block is query row 8*(r/4) + 4*g + r%4.
-template <bool MASKED>
+// The element mask of a lane's key is two row intervals [s, e): row q is masked by one iff
+// (unsigned)(q - s) < (unsigned)max(e - s, 0), one subtraction and one compare per element with the interval's
+// length formed once per unit (off_a, off_b: first row of the block's registers - s).
+template <bool MASK>
 __device__ __forceinline__ void dkdv_stage_a(const f32x16& s, const f32x16& dp, float (&t)[16],
                                              float (&u)[16], const f32x4 (&l4)[4], int e0,
-                                             int cnt, int row_base /* r0 + 32*qb + 4*g */, float sc, int b_lts,
-                                             int b_lte, int b_uts, int b_ute) {
+                                             int cnt, float sc, int off_a, unsigned len_a, int off_b, unsigned len_b) {
 #pragma unroll
   for (int r = e0; r < e0 + cnt; ++r) {
     float x = s[r];
-    if (MASKED) {
-      const int qrow = row_base + 8 * (r >> 2) + (r & 3);
-      const bool hit = ((qrow >= b_lts) & (qrow < b_lte)) | ((qrow >= b_uts) & (qrow < b_ute));
+    if (MASK) {
+      const int dr = 8 * (r >> 2) + (r & 3);   // register r is row 8*(r/4) + 4*g + r%4 of the block; 4*g is in the offsets
+      const bool hit = ((unsigned)(off_a + dr) < len_a) | ((unsigned)(off_b + dr) < len_b);
       if (hit) x = -INFINITY;
     }
     t[r] = __builtin_fmaf(x, sc, -l4[r >> 2][r & 3]);
@@ -502,12 +504,12 @@ __device__ __forceinline__ void dkdv_sync() {
 // step, and its last RD operand fetches already read the next entry's tile, so
 // the MFMA pipe does not drain between tiles.  On entry `op` holds the operands
 // of steps 0..RD-1 of this tile, on exit those of the next one.
-template <int D, bool MASKED, bool RAGGED>
+template <int D, bool MASK, bool RAGGED>
 __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, const DkdvAhead& ah,
                                           bf16x8 (&op)[DkdvCfg<D>::RD], const bf16x8 (&kreg)[D / 16],
                                           const bf16x8 (&vreg)[D / 16], f32x16 (&dkacc)[D / 32],
                                           f32x16 (&dvacc)[D / 32], int a_base, int t_base0, int t_base1, int r0,
-                                          int g, float sc, int b_lts, int b_lte, int b_uts, int b_ute) {
+                                          int g, float sc, int s_a, unsigned len_a, int s_b, unsigned len_b) {
   using C = DkdvCfg<D>;
   constexpr int NKK = D / 16, NDB = D / 32;
   constexpr int NST = 2 * NKK;     // MFMAs per block and product pair
@@ -605,8 +607,8 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
         if (stage == 0) {
           if (e0 % 4 == 0 && e0 / 4 + 1 < 4) vec_group(qb, e0 / 4 + 1);
           if (qb == 0 && e0 + EPS == 16) vec_group(1, 0);
-          dkdv_stage_a<MASKED>(sb[qb], pb[qb], tq[qb], uq[qb], l4[qb], e0, EPS, r0 + 32 * qb + 4 * g, sc,
-                       b_lts, b_lte, b_uts, b_ute);
+          dkdv_stage_a<MASK>(sb[qb], pb[qb], tq[qb], uq[qb], l4[qb], e0, EPS, sc, r0 + 32 * qb + 4 * g - s_a, len_a,
+                             r0 + 32 * qb + 4 * g - s_b, len_b);
         } else if (stage == 1) {
 #pragma unroll
           for (int r = e0; r < e0 + EPS; ++r) tq[qb][r] = fast_exp2(tq[qb][r]);
@@ -685,10 +687,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
   // out.  Tiles that need no element mask are listed first and run through the mask-free
   // instantiation, partially masked ones (for the workgroup's 128 keys) through the other;
   // keeping the two instantiations in separate loops keeps the 128 accumulator registers where
-  // they are (merged into one loop, the compiler shuffled all of them every tile).
+  // they are (merged into one loop, the compiler shuffled all of them every tile; a third loop for
+  // tiles that need only one of the two intervals made it spill inside the mask-free one).
   // Entries past the end of the list are clamped to the last one: the copies and operand
   // fetches made for them are never used, and every entry costs the same number of copies.
-#define FM_TILE_LOOP(T0, T1, MASKED)                                                                   \
+#define FM_TILE_LOOP(T0, T1, MASK)                                                                     \
   for (int t = (T0); t < (T1); ++t) {                                                                  \
     const int v_next = list[min(t + 1, n_live - 1)];                                                   \
     ah.v_copy = list[min(t + C::NSTAGE - 1, n_live - 1)];                                              \
@@ -696,8 +699,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
     ah.stage_copy = (t + C::NSTAGE - 1) % C::NSTAGE;                                                   \
     const char* st = smem + C::STAGE_OFF + (t % C::NSTAGE) * C::STAGE;                                 \
     const int r0 = (e_cur & 0xFFFFFF) * QT;                                                            \
-    dkdv_tile<D, MASKED, RAGGED>(st, (const float*)(st + C::Q_BYTES + C::DO_BYTES), ah, op, kreg, vreg, dkacc, dvacc, \
-                         a_base, t_base0, t_base1, r0, g, sc, b_lts, b_lte, b_uts, b_ute);             \
+    dkdv_tile<D, MASK, RAGGED>(st, (const float*)(st + C::Q_BYTES + C::DO_BYTES), ah, op, kreg, vreg, dkacc, dvacc, \
+                         a_base, t_base0, t_base1, r0, g, sc, b_lts, len_lt, b_uts, len_ut);           \
     e_cur = __builtin_amdgcn_readfirstlane(v_next);                                                    \
   }
 
@@ -796,6 +799,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(FmBwdArgs a)
     settle(b_lte);
     settle(b_uts);
     settle(b_ute);
+    // lengths of the key's two masked row intervals (0 for an empty one), for the element mask's compare
+    const unsigned len_lt = (unsigned)max(b_lte - b_lts, 0), len_ut = (unsigned)max(b_ute - b_uts, 0);
     async_wait<(C::NSTAGE - 2) * C::NC>();
     barrier_nofence();
     int e_cur = __builtin_amdgcn_readfirstlane(list[0]);
