@@ -223,17 +223,35 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(FmBwdArgs a) {
             __builtin_amdgcn_sched_barrier(0);
           }
           if (wcls & T_PARTIAL) {
+            // which pairs the workgroup's tile needs (1 = LT, 2 = UT, 3 = both): a pair that is not needed masks
+            // no element of the tile, and most partially masked tiles need only one
+            const int need = entry_need_pairs(entry);
+            if (need == 3) {
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-              const int kx = kb * 32 + 8 * rq + 4 * g;
-              const i32x4 bl = *(const i32x4*)(bnd + 0 * KT + kx);
-              const i32x4 be = *(const i32x4*)(bnd + 1 * KT + kx);
-              const i32x4 bu = *(const i32x4*)(bnd + 2 * KT + kx);
-              const i32x4 bv = *(const i32x4*)(bnd + 3 * KT + kx);
+              for (int rq = 0; rq < 4; ++rq) {
+                const int kx = kb * 32 + 8 * rq + 4 * g;
+                const i32x4 bl = *(const i32x4*)(bnd + 0 * KT + kx);
+                const i32x4 be = *(const i32x4*)(bnd + 1 * KT + kx);
+                const i32x4 bu = *(const i32x4*)(bnd + 2 * KT + kx);
+                const i32x4 bv = *(const i32x4*)(bnd + 3 * KT + kx);
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const bool masked = ((row >= bl[e]) & (row < be[e])) | ((row >= bu[e]) & (row < bv[e]));
-                if (masked) sacc[rq * 4 + e] = -INFINITY;
+                for (int e = 0; e < 4; ++e) {
+                  const bool masked = ((row >= bl[e]) & (row < be[e])) | ((row >= bu[e]) & (row < bv[e]));
+                  if (masked) sacc[rq * 4 + e] = -INFINITY;
+                }
+              }
+            } else {
+              const int* b_lo = bnd + (need == 2 ? 2 * KT : 0);
+#pragma unroll
+              for (int rq = 0; rq < 4; ++rq) {
+                const int kx = kb * 32 + 8 * rq + 4 * g;
+                const i32x4 bs = *(const i32x4*)(b_lo + kx);
+                const i32x4 be = *(const i32x4*)(b_lo + KT + kx);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const bool masked = (row >= bs[e]) & (row < be[e]);
+                  if (masked) sacc[rq * 4 + e] = -INFINITY;
+                }
               }
             }
             __builtin_amdgcn_sched_barrier(0);
