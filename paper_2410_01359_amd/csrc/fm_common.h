@@ -441,6 +441,10 @@ __device__ __forceinline__ void append_live(bool live, int entry, int* list, int
 //   bits 18-25 class of wave w's sub-tile in bits 18+2w, 19+2w   (0 unmasked, 1 partial, 2 fully)
 //   bits 26, 27  the workgroup's tile needs the element mask of the LT / of the UT pair (Equation 4's
 //                partial test per pair; a pair whose bit is clear masks no element of the tile)
+//   bit 28       every LT interval of the block reaches the end of the workgroup's rows (min LTE >= r1), so
+//                "row >= LTS" alone decides the LT pair;  bit 29: every UT interval starts at or above the first
+//                row (max UTS <= r0), so "row < UTE" alone decides the UT pair.  (Causal, window, document and
+//                prefix masks are all of this kind: their intervals run to row N resp. from row 0.)
 // Returns the number of entries (uniform over the workgroup).
 __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ table, int t_c, int j_begin, int j_end,
                                                      int r0, int r1, int rows_per_wave, int* list, int* wave_cnt) {
@@ -451,7 +455,8 @@ __device__ __forceinline__ int build_live_key_blocks(const int* __restrict__ tab
     if (j < j_end) {
       const MinMax8 mm = load_minmax(table, t_c, j);
       cls = classify_tile(r0, r1, mm);
-      entry = (j - j_begin) | ((cls & 3) << 16) | (((cls >> 4) & 3) << 26);
+      entry = (j - j_begin) | ((cls & 3) << 16) | (((cls >> 4) & 3) << 26) | ((mm.v[LTE_MIN] >= r1 ? 1 : 0) << 28) |
+              ((mm.v[UTS_MAX] <= r0 ? 1 : 0) << 29);
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const int w0 = min(r0 + w * rows_per_wave, r1), w1 = min(w0 + rows_per_wave, r1);
@@ -467,6 +472,14 @@ __device__ __forceinline__ int entry_tile_class(int entry) { return (entry >> 16
 __device__ __forceinline__ int entry_wave_class(int entry, int wave) { return (entry >> (18 + 2 * wave)) & 3; }
 // 1 = LT pair only, 2 = UT pair only, 3 = both (0 only for tiles that are not partially masked)
 __device__ __forceinline__ int entry_need_pairs(int entry) { return (entry >> 26) & 3; }
+// The same with 4 added where the one pair needed is decided by a single comparison per element (bits 28, 29):
+// 5 = "row >= LTS", 6 = "row < UTE".
+__device__ __forceinline__ int entry_mask_mode(int entry) {
+  const int need = (entry >> 26) & 3;
+  if (need == 1 && ((entry >> 28) & 1)) return 5;
+  if (need == 2 && ((entry >> 29) & 1)) return 6;
+  return need;
+}
 
 // Column-parallel loop: classify row blocks [i_begin, i_end) of block_r rows
 // against one key block's min/max values; entries are i | class << 24.  The

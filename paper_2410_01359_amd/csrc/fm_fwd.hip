@@ -72,7 +72,8 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
     const int* bnd_g = (const int*)((const char*)bnd + opaque(16 * w.g));
     // A sub-tile that Equation 4 proves fully masked for this wave takes the same path and ends
     // with every score at -inf.  `masked` says which pairs the workgroup's tile needs (1 = LT,
-    // 2 = UT, 3 = both): a pair that is not needed masks no element of the tile, so leaving it
+    // 2 = UT, 3 = both; 5, 6 = one pair that a single comparison decides, see entry_mask_mode):
+    // a pair that is not needed masks no element of the tile, so leaving it
     // out is exact -- and most partially masked tiles (a causal diagonal, a window edge, a
     // document boundary) need only one.
     if (masked == 3) {
@@ -92,6 +93,32 @@ __device__ __forceinline__ void fwd_step(f32x16 (&cur)[2], f32x16 (&nxt)[2], f32
           }
           __builtin_amdgcn_sched_barrier(0);  // keep the bound reads of later steps from piling up in registers
         }
+    } else if (masked & 4) {
+      // one pair, decided by one comparison per element (5: row >= LTS, 6: row < UTE): one bound per key
+      const int* b_one = bnd_g + (masked == 5 ? 0 : 3 * KT);
+      if (masked == 5) {
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const i32x4 bs = *(const i32x4*)(b_one + kb * 32 + 8 * rq);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (w.row >= bs[e]) cur[kb][rq * 4 + e] = -INFINITY;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const i32x4 be = *(const i32x4*)(b_one + kb * 32 + 8 * rq);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (w.row < be[e]) cur[kb][rq * 4 + e] = -INFINITY;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      }
     } else {
       const int* b_lo = bnd_g + (masked == 2 ? 2 * KT : 0);   // starts of the one pair that is needed
 #pragma unroll
@@ -310,7 +337,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void fwd_kernel(FmFwdArgs a) 
     const char* vs_ = smem + C::V_OFF + ((T) & 1) * C::VSTAGE;                                   \
     fwd_step<D>(CUR, NXT, oacc, qreg, m_run, l_run, smem + C::K_OFF + (((T) + 1) & 1) * C::K_BYTES, vs_, \
                 (const int*)(vs_ + C::V_BYTES),                                                  \
-                entry_wave_class(e_t, wave) != T_UNMASKED ? entry_need_pairs(e_t) : 0, w);       \
+                entry_wave_class(e_t, wave) != T_UNMASKED ? entry_mask_mode(e_t) : 0, w);        \
     async_wait<0>();   /* K(T+2) and V(T+1) have landed ... */                                   \
     barrier_nofence(); /* ... for every wave, and every wave is done with K(T+1) and V(T) */     \
     e_t = e_1;                                                                                   \
