@@ -581,9 +581,11 @@ __device__ __forceinline__ void dkdv_tile(const char* qs, const float* vec_s, co
         else
           dvacc[db] = mfma32(op[x % RD], pa[qb][h], dvacc[db]);
       } else if (u & 1) {
-        mfma32_acc(dkacc[db], op[x % RD], dsa[qb][h], db == 0);   // db == 0: first reader of dsa[qb][h]
+        // dsa[qb][h] / pa[qb][h] were converted several steps ago (the vector work of a block ends before the
+        // block's dV, dK steps begin), so no idle instruction is needed in front of their first reader
+        mfma32_acc(dkacc[db], op[x % RD], dsa[qb][h], false);
       } else {
-        mfma32_acc(dvacc[db], op[x % RD], pa[qb][h], db == 0);    // ... of pa[qb][h]
+        mfma32_acc(dvacc[db], op[x % RD], pa[qb][h], false);
       }
     }
     // --- the workgroup step and the copies behind it
